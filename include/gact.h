@@ -1,0 +1,159 @@
+/*
+ * gact.h -- C ABI of the MI355X (gfx950) activation compressor / decompressor
+ * of GACT (arXiv 2206.11357) and its host-side bit allocator.
+ *
+ * What the calls compute
+ *   The paper's compressor Q is a per-group stochastic-rounding quantizer
+ *   (Sec. 5: "per-group quantizer"; App. A.4: transform
+ *   T(h_j) = (2^b-1)(h_j - min h)/(max h - min h), round up with probability
+ *   T - floor(T), otherwise down, and map back with the inverse of T).  A
+ *   context tensor is a flattened vector (Sec. 3.1); it is cut into groups of
+ *   `group_size` consecutive elements, the last group may be shorter.
+ *   Per-tensor bit widths b_l come from Eq. (ilp) of Sec. 4.1,
+ *   min sum_l c_l S(b_l) s.t. sum_l b_l D_l <= budget, S(b) = (2^b-1)^-2.
+ *
+ * Arithmetic (bit-exact contract)
+ *   IEEE binary32, round to nearest even, every operation rounded on its own
+ *   (no fused multiply-add where it would change a result):
+ *     mn = min, mx = max over the group;  mn = mn + 0.0f (so -0 is stored as +0)
+ *     range = mx - mn;  B = 2^bits - 1
+ *     range >= 2^-100 :  inv = B / range,  step = range / B
+ *     otherwise       :  inv = 0,          step = 0        (constant group)
+ *     t = (x - mn) * inv;  q = floor(t) + (u < t - floor(t));  q = min(q, B)
+ *     y = q * step + mn                  (decompress; bf16 output rounds y RNE)
+ *   Rounding noise u for element i of a tensor compressed with `seed`:
+ *   Philox4x32-10 (Salmon et al., SC'11), key = (low, high 32 bits of seed),
+ *   counter = (low, high 32 bits of i/8, 0, 0).  The four output words hold
+ *   eight 16-bit slots, low half first; element i takes slot i%8 and
+ *   u = (slot + 0.5) / 65536.  The stream is a function of (seed, i) only, so
+ *   results never depend on launch shape or on single- vs multi-tensor calls,
+ *   and the same seed replays the same compression (Alg. 1 of the paper relies
+ *   on replayable per-tensor seeds).
+ *
+ * Layouts
+ *   packed : linear bit string, element i in bits [i*bits, (i+1)*bits), bit k
+ *            of the string is bit k%8 of byte k/8 (little-endian, LSB first).
+ *            gact_packed_bytes(n, bits) bytes; all pad bits are written as 0.
+ *   gmin   : float[gact_num_groups]  group minimum.
+ *   gscale : float[gact_num_groups]  dequantisation step, range / (2^bits-1).
+ *
+ * Memory and ownership
+ *   Pointers named d_* are DEVICE pointers owned by the caller; h_* are HOST
+ *   pointers.  The library allocates nothing, frees nothing and keeps no
+ *   pointer after a call returns.  d_x, d_y, d_packed and the multi-tensor
+ *   workspace must be 16-byte aligned; d_gmin / d_gscale 4-byte aligned.
+ *   Device calls enqueue work on `stream` (a hipStream_t passed as void*;
+ *   NULL is the default stream) and return without waiting for it.
+ *
+ * Errors
+ *   Every call returns GACT_OK or a negative code; on error nothing has been
+ *   enqueued.  Inputs must be finite with max - min finite; NaN / Inf give
+ *   unspecified values but never an out-of-bounds access.
+ */
+#ifndef GACT_H
+#define GACT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { GACT_F32 = 0, GACT_BF16 = 1 } gact_dtype;
+
+enum {
+    GACT_OK       =  0,
+    GACT_E_ARG    = -1,  /* null pointer, n < 0, misaligned pointer, bad dtype, L < 0,
+                            negative / non-finite sensitivity or numel, workspace too small */
+    GACT_E_BITS   = -2,  /* bits not in {1,2,4,8} */
+    GACT_E_GROUP  = -3,  /* group_size not a multiple of 32 in [32, 1024] */
+    GACT_E_BUDGET = -4,  /* avg_bit_budget < 1 or NaN: no feasible scheme */
+    GACT_E_HIP    = -5   /* the HIP runtime refused the launch or copy */
+};
+
+/* ceil(n / group_size); 0 when n <= 0 or group_size <= 0. */
+size_t gact_num_groups(int64_t n, int group_size);
+
+/* ceil(n * bits / 8) rounded up to a multiple of 16; 0 when n <= 0. */
+size_t gact_packed_bytes(int64_t n, int bits);
+
+/* Human-readable name of an error code (static string). */
+const char *gact_error_string(int code);
+
+/*
+ * Compressor (forward pass; App. A.4 applied per group, Sec. 5).
+ *   d_x      in   n elements of `dtype`, contiguous, not modified
+ *   d_packed out  gact_packed_bytes(n, bits) bytes
+ *   d_gmin   out  gact_num_groups(n, group_size) floats
+ *   d_gscale out  same count
+ * n == 0 is GACT_OK and launches nothing.
+ */
+int gact_compress(const void *d_x, gact_dtype dtype, int64_t n, int group_size,
+                  int bits, uint64_t seed, void *d_packed, float *d_gmin,
+                  float *d_gscale, void *stream);
+
+/*
+ * Decompressor (backward pass; inverse transform of App. A.4).
+ *   d_y out  n elements of `dtype`.  Must not overlap the inputs.
+ */
+int gact_decompress(const void *d_packed, const float *d_gmin,
+                    const float *d_gscale, int64_t n, int group_size, int bits,
+                    void *d_y, gact_dtype dtype, void *stream);
+
+/*
+ * Multi-tensor launches: the many saved tensors of one iteration (the paper's
+ * hook compresses every saved tensor of every operator, Sec. 5) in one launch
+ * per direction.  Each descriptor carries its own element count, dtype, bits
+ * and seed (the per-tensor seeds r_l of Alg. 1).  The result for each tensor
+ * is byte-identical to the single-tensor call with the same arguments.
+ *
+ *   h_descs          host array of L descriptors; device pointers inside.
+ *                    compress reads x and writes packed/gmin/gscale (y unused);
+ *                    decompress reads packed/gmin/gscale and writes y (x unused).
+ *   d_workspace      device scratch of at least gact_multi_workspace_bytes(L)
+ *                    bytes, 16-byte aligned; holds the launch table until the
+ *                    enqueued kernel has run, so it must not be reused for a
+ *                    different table before then.
+ * The table is copied from a staging area the call owns for its duration with
+ * a stream-ordered copy; h_descs may be reused as soon as the call returns.
+ * L == 0, or all n == 0, is GACT_OK and launches nothing.
+ */
+typedef struct {
+    const void *x;
+    void       *packed;
+    float      *gmin;
+    float      *gscale;
+    void       *y;
+    int64_t     n;
+    uint64_t    seed;
+    int32_t     bits;
+    int32_t     dtype;     /* gact_dtype */
+} gact_tensor_desc;
+
+size_t gact_multi_workspace_bytes(int L);
+
+int gact_compress_multi(const gact_tensor_desc *h_descs, int L, int group_size,
+                        void *d_workspace, size_t workspace_bytes, void *stream);
+
+int gact_decompress_multi(const gact_tensor_desc *h_descs, int L, int group_size,
+                          void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Bit allocator (host only, synchronous; Eq. (ilp), Sec. 4.1-4.2).
+ *   h_sensitivity in  c_l >= 0, finite, L floats (Alg. 1's estimate)
+ *   h_numel       in  D_l >= 0, L values
+ *   avg_bit_budget    budget = floor(avg * sum_l D_l) bits; must be >= 1
+ *   h_bits_out    out b_l in {1,2,4,8}
+ * Greedy descent from 8 bits: repeatedly apply the one-level step
+ * (8->4, 4->2, 2->1 of one tensor) with the least added variance per bit
+ * saved, c_l (S(lo) - S(hi)) / (D_l (hi - lo)) in binary64, ties to the lowest
+ * index, until sum b_l D_l <= budget.  Tensors with D_l = 0 keep 8.
+ */
+int gact_allocate_bits(const float *h_sensitivity, const int64_t *h_numel, int L,
+                       double avg_bit_budget, int32_t *h_bits_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GACT_H */
