@@ -1,0 +1,244 @@
+// Host side of the C ABI declared in include/gact.h: argument checks, launch
+// geometry, the multi-tensor launch table, and the bit allocator (Eq. (ilp) of
+// arXiv 2206.11357, Sec. 4.1, solved by greedy descent with a binary heap).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstring>
+#include <queue>
+#include <vector>
+
+#include "gact.h"
+#include "gact_device.h"
+
+namespace {
+
+constexpr int kPerLane = 32;
+constexpr int kWavesPerBlock = 4;
+
+bool bits_ok(int bits) { return bits == 1 || bits == 2 || bits == 4 || bits == 8; }
+bool group_ok(int g) { return g >= 32 && g <= 1024 && g % 32 == 0; }
+bool dtype_ok(int dt) { return dt == GACT_F32 || dt == GACT_BF16; }
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+gact::Geometry make_geometry(int group_size) {
+    gact::Geometry geo;
+    geo.lpg = group_size / kPerLane;
+    geo.lanes_used = (64 / geo.lpg) * geo.lpg;
+    geo.pow2 = (geo.lpg & (geo.lpg - 1)) == 0 ? 1 : 0;
+    geo.group_size = group_size;
+    return geo;
+}
+
+int64_t tiles_for(int64_t n, const gact::Geometry& geo) {
+    const int64_t te = (int64_t)geo.lanes_used * kPerLane;
+    return (n + te - 1) / te;
+}
+
+// Fills `out`; returns GACT_OK or the error for this tensor.
+int make_args(bool compress, const void* x, void* packed, float* gmin, float* gscale, void* y,
+              int64_t n, uint64_t seed, int bits, int dtype, const gact::Geometry& geo,
+              gact::TensorArgs* out) {
+    if (!bits_ok(bits)) return GACT_E_BITS;
+    if (n < 0 || !dtype_ok(dtype)) return GACT_E_ARG;
+    if (n > 0) {
+        const void* io = compress ? x : y;
+        if (!io || !packed || !gmin || !gscale) return GACT_E_ARG;
+        if (!aligned(io, 16) || !aligned(packed, 16) || !aligned(gmin, 4) || !aligned(gscale, 4))
+            return GACT_E_ARG;
+    }
+    out->x = x;
+    out->packed = packed;
+    out->gmin = gmin;
+    out->gscale = gscale;
+    out->y = y;
+    out->n = n;
+    out->tiles = tiles_for(n, geo);
+    out->packed_words = (int64_t)(gact_packed_bytes(n, bits) / 4);
+    out->seed_lo = (uint32_t)seed;
+    out->seed_hi = (uint32_t)(seed >> 32);
+    out->bits = bits;
+    out->dtype = dtype;
+    return GACT_OK;
+}
+
+int run_single(bool compress, const gact::TensorArgs& t, const gact::Geometry& geo, void* stream) {
+    if (t.n == 0) return GACT_OK;
+    const int64_t blocks = (t.tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (blocks > 0x7FFFFFFFll) return GACT_E_ARG;
+    return gact_launch_single(compress ? 1 : 0, &t, &geo, (unsigned)blocks, stream) == 0
+               ? GACT_OK : GACT_E_HIP;
+}
+
+size_t table_bytes(int L) { return ((size_t)L * sizeof(gact::TensorArgs) + 15) / 16 * 16; }
+
+int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_size,
+              void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (L < 0) return GACT_E_ARG;
+    if (!group_ok(group_size)) return GACT_E_GROUP;
+    if (L == 0) return GACT_OK;
+    if (!descs) return GACT_E_ARG;
+    const gact::Geometry geo = make_geometry(group_size);
+
+    // one contiguous staging image: table of the non-empty tensors, then the
+    // first block of each, then the total
+    std::vector<gact::TensorArgs> table;
+    std::vector<uint32_t> first;
+    table.reserve(L);
+    first.reserve(L + 1);
+    uint64_t blocks = 0;
+    for (int l = 0; l < L; ++l) {
+        const gact_tensor_desc& d = descs[l];
+        gact::TensorArgs t;
+        const int rc = make_args(compress, d.x, d.packed, d.gmin, d.gscale, d.y, d.n, d.seed,
+                                 d.bits, d.dtype, geo, &t);
+        if (rc != GACT_OK) return rc;
+        if (d.n == 0) continue;
+        first.push_back((uint32_t)blocks);
+        table.push_back(t);
+        blocks += (uint64_t)((t.tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+        if (blocks > 0x7FFFFFFFull) return GACT_E_ARG;
+    }
+    const int live = (int)table.size();
+    if (live == 0) return GACT_OK;
+    first.push_back((uint32_t)blocks);
+
+    if (!d_workspace || !aligned(d_workspace, 16) ||
+        workspace_bytes < gact_multi_workspace_bytes(L))
+        return GACT_E_ARG;
+
+    const size_t tb = table_bytes(live);
+    std::vector<unsigned char> image(tb + first.size() * sizeof(uint32_t));
+    std::memcpy(image.data(), table.data(), (size_t)live * sizeof(gact::TensorArgs));
+    std::memcpy(image.data() + tb, first.data(), first.size() * sizeof(uint32_t));
+    // pageable source: the runtime has taken its own copy when this returns
+    if (hipMemcpyAsync(d_workspace, image.data(), image.size(), hipMemcpyHostToDevice,
+                       (hipStream_t)stream) != hipSuccess)
+        return GACT_E_HIP;
+    const gact::TensorArgs* d_table = (const gact::TensorArgs*)d_workspace;
+    const uint32_t* d_first = (const uint32_t*)((const unsigned char*)d_workspace + tb);
+    return gact_launch_multi(compress ? 1 : 0, d_table, d_first, live, &geo, (unsigned)blocks,
+                             stream) == 0 ? GACT_OK : GACT_E_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t gact_num_groups(int64_t n, int group_size) {
+    if (n <= 0 || group_size <= 0) return 0;
+    return (size_t)((n + group_size - 1) / group_size);
+}
+
+size_t gact_packed_bytes(int64_t n, int bits) {
+    if (n <= 0 || bits <= 0) return 0;
+    const uint64_t bytes = ((uint64_t)n * (uint64_t)bits + 7) / 8;
+    return (size_t)((bytes + 15) / 16 * 16);
+}
+
+const char* gact_error_string(int code) {
+    switch (code) {
+        case GACT_OK: return "ok";
+        case GACT_E_ARG: return "bad argument (null/misaligned pointer, negative size, bad dtype, small workspace)";
+        case GACT_E_BITS: return "bits must be 1, 2, 4 or 8";
+        case GACT_E_GROUP: return "group_size must be a multiple of 32 in [32, 1024]";
+        case GACT_E_BUDGET: return "avg_bit_budget must be >= 1";
+        case GACT_E_HIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}
+
+int gact_compress(const void* d_x, gact_dtype dtype, int64_t n, int group_size, int bits,
+                  uint64_t seed, void* d_packed, float* d_gmin, float* d_gscale, void* stream) {
+    if (!bits_ok(bits)) return GACT_E_BITS;
+    if (!group_ok(group_size)) return GACT_E_GROUP;
+    const gact::Geometry geo = make_geometry(group_size);
+    gact::TensorArgs t;
+    const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, bits,
+                             (int)dtype, geo, &t);
+    if (rc != GACT_OK) return rc;
+    return run_single(true, t, geo, stream);
+}
+
+int gact_decompress(const void* d_packed, const float* d_gmin, const float* d_gscale, int64_t n,
+                    int group_size, int bits, void* d_y, gact_dtype dtype, void* stream) {
+    if (!bits_ok(bits)) return GACT_E_BITS;
+    if (!group_ok(group_size)) return GACT_E_GROUP;
+    const gact::Geometry geo = make_geometry(group_size);
+    gact::TensorArgs t;
+    const int rc = make_args(false, nullptr, const_cast<void*>(d_packed),
+                             const_cast<float*>(d_gmin), const_cast<float*>(d_gscale), d_y, n, 0,
+                             bits, (int)dtype, geo, &t);
+    if (rc != GACT_OK) return rc;
+    return run_single(false, t, geo, stream);
+}
+
+size_t gact_multi_workspace_bytes(int L) {
+    if (L <= 0) return 0;
+    return table_bytes(L) + ((size_t)(L + 1) * sizeof(uint32_t) + 15) / 16 * 16;
+}
+
+int gact_compress_multi(const gact_tensor_desc* h_descs, int L, int group_size, void* d_workspace,
+                        size_t workspace_bytes, void* stream) {
+    return run_multi(true, h_descs, L, group_size, d_workspace, workspace_bytes, stream);
+}
+
+int gact_decompress_multi(const gact_tensor_desc* h_descs, int L, int group_size,
+                          void* d_workspace, size_t workspace_bytes, void* stream) {
+    return run_multi(false, h_descs, L, group_size, d_workspace, workspace_bytes, stream);
+}
+
+// ---------------------------------------------------------------- allocator
+int gact_allocate_bits(const float* h_sensitivity, const int64_t* h_numel, int L,
+                       double avg_bit_budget, int32_t* h_bits_out) {
+    if (L < 0) return GACT_E_ARG;
+    if (!(avg_bit_budget >= 1.0)) return GACT_E_BUDGET;
+    if (L == 0) return GACT_OK;
+    if (!h_sensitivity || !h_numel || !h_bits_out) return GACT_E_ARG;
+
+    static const int level[4] = {1, 2, 4, 8};
+    double S[4];
+    for (int k = 0; k < 4; ++k) {
+        const double B = (double)((1 << level[k]) - 1);
+        S[k] = 1.0 / (B * B);
+    }
+    uint64_t total = 0;
+    for (int l = 0; l < L; ++l) {
+        const double c = (double)h_sensitivity[l];
+        if (!(c >= 0.0) || std::isinf(c) || h_numel[l] < 0) return GACT_E_ARG;
+        total += (uint64_t)h_numel[l];
+    }
+    const double cap = std::floor(avg_bit_budget * (double)total);
+    const uint64_t budget = cap >= 18446744073709549568.0 ? UINT64_MAX : (uint64_t)cap;
+    uint64_t used = 8u * total;
+
+    // cost of moving tensor l from level index k to k-1: variance added per bit saved
+    auto step_key = [&](int l, int k) {
+        return ((double)h_sensitivity[l] * (S[k - 1] - S[k])) /
+               ((double)h_numel[l] * (double)(level[k] - level[k - 1]));
+    };
+    struct Step { double key; int l; };
+    struct Later {   // min-heap on (key, l)
+        bool operator()(const Step& a, const Step& b) const {
+            return a.key > b.key || (a.key == b.key && a.l > b.l);
+        }
+    };
+    std::vector<int> idx((size_t)L, 3);
+    std::priority_queue<Step, std::vector<Step>, Later> heap;
+    for (int l = 0; l < L; ++l) {
+        h_bits_out[l] = 8;
+        if (h_numel[l] > 0) heap.push(Step{step_key(l, 3), l});
+    }
+    while (used > budget && !heap.empty()) {
+        const Step s = heap.top();
+        heap.pop();
+        const int k = idx[(size_t)s.l];
+        used -= (uint64_t)h_numel[s.l] * (uint64_t)(level[k] - level[k - 1]);
+        idx[(size_t)s.l] = k - 1;
+        h_bits_out[s.l] = level[k - 1];
+        if (k - 1 > 0) heap.push(Step{step_key(s.l, k - 1), s.l});
+    }
+    return GACT_OK;
+}
+
+}  // extern "C"

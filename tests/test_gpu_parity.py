@@ -1,0 +1,268 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle on the
+same seeded inputs.  Packed codes, group minima and steps must be bit-exact;
+dequantised values within 1e-6 relative (fp32) / one bf16 ulp -- in practice
+they are compared for equality first and the tolerance is the stated bar.
+Quantizer: arXiv 2206.11357 App. A.4, per group (Sec. 5)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import synthetic_inputs as syn
+
+pytestmark = pytest.mark.gpu
+
+CANARY = 0xA5
+PAD = 256        # guard bytes after every output buffer
+
+
+def to_device(x_np):
+    """numpy float32 / uint16(bf16 bits) -> device tensor of the matching dtype"""
+    if x_np.dtype == np.uint16:
+        return torch.from_numpy(x_np.view(np.int16).copy()).cuda().view(torch.bfloat16)
+    return torch.from_numpy(x_np).cuda()
+
+
+def to_host(t):
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def guarded(nbytes, dtype):
+    """A buffer of nbytes followed by PAD canary bytes; returns (view, whole)."""
+    whole = torch.full((nbytes + PAD,), CANARY, dtype=torch.uint8, device="cuda")
+    return whole[:nbytes].view(dtype), whole
+
+
+def canary_intact(whole, nbytes):
+    return bool((whole[nbytes:] == CANARY).all().item())
+
+
+def run_case(gact, x_np, G, bits, seed, check_y=True):
+    """Compress + decompress on the GPU with guarded buffers; compare to oracle."""
+    n = x_np.size
+    x = to_device(x_np)
+    x_before = x.clone()
+    pb = gact.gact_packed_bytes(n, bits)
+    ng = gact.gact_num_groups(n, G)
+    packed, packed_w = guarded(pb, torch.uint8)
+    gmin, gmin_w = guarded(ng * 4, torch.float32)
+    gscale, gscale_w = guarded(ng * 4, torch.float32)
+    gact.gact_compress(x, G, bits, seed, packed, gmin, gscale)
+    y, y_w = guarded(n * x.element_size(), x.dtype)
+    gact.gact_decompress(packed, gmin, gscale, n, G, bits, y=y)
+    torch.cuda.synchronize()
+
+    p_ref, mn_ref, sc_ref = oracle.compress(x_np, G, bits, seed)
+    assert torch.equal(x, x_before), "compress modified its input"
+    assert canary_intact(packed_w, pb) and canary_intact(gmin_w, ng * 4)
+    assert canary_intact(gscale_w, ng * 4) and canary_intact(y_w, n * x.element_size())
+    mn, sc, p = to_host(gmin), to_host(gscale), to_host(packed)
+    assert np.array_equal(mn.view(np.uint32), mn_ref.view(np.uint32)), "gmin differs"
+    assert np.array_equal(sc.view(np.uint32), sc_ref.view(np.uint32)), "gscale differs"
+    if not np.array_equal(p, p_ref):
+        bad = np.flatnonzero(p != p_ref)
+        raise AssertionError("packed differs at %d bytes, first %s" % (bad.size, bad[:8]))
+    if check_y:
+        dt = oracle.BF16 if x_np.dtype == np.uint16 else oracle.F32
+        y_ref = oracle.decompress(p_ref, mn_ref, sc_ref, n, G, bits, dt)
+        y_h = to_host(y)
+        if dt == oracle.F32:
+            # bar: 1e-6 relative; the two sides run the same two roundings
+            assert np.allclose(y_h, y_ref, rtol=1e-6, atol=0)
+            assert np.array_equal(y_h.view(np.uint32), y_ref.view(np.uint32))
+        else:
+            # bar: one bf16 ulp
+            assert np.all(np.abs(y_h.astype(np.int32) - y_ref.astype(np.int32)) <= 1)
+            assert np.array_equal(y_h, y_ref)
+    return p, mn, sc
+
+
+# ------------------------------------------------------------------ config 1
+def test_config1_single_tensor(gact):
+    c = syn.config1()
+    run_case(gact, c["x"], c["group_size"], c["bits"], c["seed"])
+
+
+# ------------------------------------------------- sizes, tiles, ragged tails
+@pytest.mark.parametrize("dtype", ("f32", "bf16"))
+@pytest.mark.parametrize("bits", (1, 2, 4, 8))
+@pytest.mark.parametrize("G", (32, 128, 256, 1024))
+def test_tiles_and_ragged_tails(gact, dtype, bits, G):
+    # several wavefront tiles (2048 elements) and blocks (8192), ends inside a
+    # tile, inside a group, inside a 16-byte load and inside a Philox block
+    for n in (1, 5, 31, 33, 2048, 2049, 8192 + 7, 5 * 8192 + 3 * 256 + 129, 40000 - 1):
+        x = syn.draw_numpy(syn.OUTLIER, n, 100 + n % 97)
+        if dtype == "bf16":
+            x = syn.f32_to_bf16_bits(x)
+        run_case(gact, x, G, bits, seed=n + bits)
+
+
+@pytest.mark.parametrize("dtype", ("f32", "bf16"))
+@pytest.mark.parametrize("G", (64, 96, 160, 352, 512, 736, 992))
+def test_other_group_sizes(gact, dtype, G):
+    for n, bits in ((G * 70 + 13, 2), (G * 21, 1), (G * 64, 4), (3 * G - 1, 8), (2016 * 3, 1)):
+        x = syn.draw_numpy(syn.NORMAL, n, G + bits)
+        if dtype == "bf16":
+            x = syn.f32_to_bf16_bits(x)
+        run_case(gact, x, G, bits, seed=G)
+
+
+def test_value_laws_of_the_workloads(gact):
+    # half-zero ReLU outputs, GELU outputs, softmax rows (values in [0,1], skewed)
+    for law, row, dtype, G, bits in ((syn.RELU, 0, "f32", 256, 2), (syn.RELU, 0, "f32", 256, 4),
+                                     (syn.SOFTMAX, 512, "bf16", 256, 4), (syn.GELU, 0, "bf16", 128, 2),
+                                     (syn.SOFTMAX, 197, "bf16", 128, 8), (syn.NORMAL, 0, "bf16", 128, 1)):
+        n = 197 * 512 * 3 if law == syn.SOFTMAX else 100000
+        x = syn.draw_numpy(law, n, 7, row)
+        if dtype == "bf16":
+            x = syn.f32_to_bf16_bits(x)
+        run_case(gact, x, G, bits, seed=3)
+
+
+# ------------------------------------------------------------ degenerate cases
+@pytest.mark.parametrize("bits", (1, 2, 4, 8))
+def test_constant_zero_tiny_range_and_signed_zero_groups(gact, bits):
+    G = 64
+    x = syn.draw_numpy(syn.NORMAL, 40 * G, 1)
+    x[0:G] = 3.25                       # constant
+    x[G:2 * G] = 0.0
+    x[G + 5] = -0.0                     # signed zeros only
+    x[2 * G:3 * G] = 1e-30
+    x[2 * G + 1] = np.float32(1e-30) + np.float32(2.0**-110)      # range below 2^-100
+    x[3 * G:4 * G] = np.abs(x[3 * G:4 * G]); x[3 * G + 9] = -0.0   # minimum is -0
+    x[4 * G:5 * G] = np.float32(2.0**-100) * np.arange(G)          # range just above the threshold
+    x[5 * G:6 * G] = 1e30 * x[5 * G:6 * G]                         # large magnitudes
+    x[6 * G:7 * G] = -5.0; x[6 * G + 63] = 5.0                     # two-valued
+    p, mn, sc = run_case(gact, x, G, bits, seed=9)
+    assert sc[0] == 0 and sc[1] == 0 and sc[2] == 0
+    assert not np.signbit(mn[1]) and not np.signbit(mn[3])
+
+
+@pytest.mark.parametrize("bits", (1, 2, 4, 8))
+def test_on_grid_inputs_round_trip_exactly(gact, bits):
+    B = 2 ** bits - 1
+    G = 256
+    rng = np.random.default_rng(bits)
+    j = rng.integers(0, B + 1, size=16 * G)
+    j[::G] = 0
+    j[1::G] = B
+    x = (np.float32(-4.0) + j * np.float32(0.125)).astype(np.float32)
+    xd = torch.from_numpy(x).cuda()
+    for seed in (0, 1, 2**40 + 17):
+        packed, gmin, gscale = gact.gact_compress(xd, G, bits, seed)
+        y = gact.gact_decompress(packed, gmin, gscale, x.size, G, bits)
+        assert torch.equal(y, xd)
+    run_case(gact, x, G, bits, seed=5)
+
+
+def test_top_code_is_clamped_under_eight_bits(gact):
+    # many groups whose (max-min)*fl(255/(max-min)) overshoots 255 by an ulp
+    x = syn.draw_numpy(syn.NORMAL, 32 * 20000, 2)
+    p, mn, sc = run_case(gact, x, 32, 8, seed=11, check_y=False)
+    top = x.reshape(-1, 32).argmax(1) + np.arange(20000) * 32
+    assert np.all(p[top] >= 254)
+
+
+def test_non_finite_inputs_do_not_write_out_of_bounds(gact):
+    x = syn.draw_numpy(syn.NORMAL, 5000, 3)
+    x[17] = np.nan; x[300] = np.inf; x[2100] = -np.inf; x[4999] = np.nan
+    xd = torch.from_numpy(x).cuda()
+    n, G, bits = x.size, 128, 4
+    pb, ng = gact.gact_packed_bytes(n, bits), gact.gact_num_groups(n, G)
+    packed, pw = guarded(pb, torch.uint8)
+    gmin, mw = guarded(ng * 4, torch.float32)
+    gscale, sw = guarded(ng * 4, torch.float32)
+    y, yw = guarded(n * 4, torch.float32)
+    gact.gact_compress(xd, G, bits, 1, packed, gmin, gscale)
+    gact.gact_decompress(packed, gmin, gscale, n, G, bits, y=y)
+    torch.cuda.synchronize()
+    assert canary_intact(pw, pb) and canary_intact(mw, ng * 4) and canary_intact(sw, ng * 4)
+    assert canary_intact(yw, n * 4)
+
+
+# ------------------------------------------------------- seeds and large index
+def test_seed_words_and_replay(gact):
+    x = syn.draw_numpy(syn.NORMAL, 10000, 4)
+    for seed in (0, 1, 0xFFFFFFFF, 1 << 32, 0x0123456789ABCDEF, 2**64 - 1):
+        run_case(gact, x, 256, 2, seed, check_y=False)
+    xd = torch.from_numpy(x).cuda()
+    a = gact.gact_compress(xd, 256, 2, 77)
+    b = gact.gact_compress(xd, 256, 2, 77)
+    c = gact.gact_compress(xd, 256, 2, 78)
+    assert torch.equal(a[0], b[0]) and not torch.equal(a[0], c[0])
+    assert torch.equal(a[1], c[1]) and torch.equal(a[2], c[2])
+
+
+# ------------------------------------------------------------------ multi-tensor
+def multi_case(gact, specs, G):
+    """specs: list of (x_np, bits, seed).  Runs both multi calls with guarded
+    buffers and compares every tensor with the oracle and the single calls."""
+    L = len(specs)
+    xs = [to_device(x) if x.size else torch.empty(0, device="cuda", dtype=torch.float32 if x.dtype == np.float32 else torch.bfloat16) for x, _, _ in specs]
+    ns = [x.size for x, _, _ in specs]
+    bits = [b for _, b, _ in specs]
+    seeds = [s for _, _, s in specs]
+    dts = [t.dtype for t in xs]
+    bufs = []
+    for l in range(L):
+        pb, ng = gact.gact_packed_bytes(ns[l], bits[l]), gact.gact_num_groups(ns[l], G)
+        bufs.append((guarded(pb, torch.uint8), guarded(ng * 4, torch.float32),
+                     guarded(ng * 4, torch.float32), guarded(ns[l] * xs[l].element_size(), dts[l]),
+                     pb, ng))
+    descs = gact.make_descs(xs, [b[0][0] for b in bufs], [b[1][0] for b in bufs],
+                            [b[2][0] for b in bufs], [b[3][0] for b in bufs], ns, bits, seeds, dts)
+    ws = torch.empty(gact.gact_multi_workspace_bytes(L), dtype=torch.uint8, device="cuda")
+    gact.gact_compress_multi(descs, L, G, ws)
+    gact.gact_decompress_multi(descs, L, G, ws)
+    torch.cuda.synchronize()
+    for l, (x_np, b, s) in enumerate(specs):
+        (p, pw), (mn, mw), (sc, sw), (y, yw), pb, ng = bufs[l]
+        assert canary_intact(pw, pb) and canary_intact(mw, ng * 4) and canary_intact(sw, ng * 4)
+        assert canary_intact(yw, ns[l] * xs[l].element_size())
+        if ns[l] == 0:
+            continue
+        p_ref, mn_ref, sc_ref = oracle.compress(x_np, G, b, s)
+        dt = oracle.BF16 if x_np.dtype == np.uint16 else oracle.F32
+        y_ref = oracle.decompress(p_ref, mn_ref, sc_ref, ns[l], G, b, dt)
+        assert np.array_equal(to_host(p), p_ref), l
+        assert np.array_equal(to_host(mn).view(np.uint32), mn_ref.view(np.uint32)), l
+        assert np.array_equal(to_host(sc).view(np.uint32), sc_ref.view(np.uint32)), l
+        yh = to_host(y)
+        assert np.array_equal(yh.view(np.uint32) if dt == oracle.F32 else yh,
+                              y_ref.view(np.uint32) if dt == oracle.F32 else y_ref), l
+        # single-tensor call gives the same bytes (launch-shape independence)
+        p1, mn1, sc1 = gact.gact_compress(xs[l], G, b, s)
+        assert torch.equal(p1, p) and torch.equal(mn1, mn) and torch.equal(sc1, sc)
+
+
+@pytest.mark.parametrize("G", (128, 256, 96))
+def test_multi_tensor_mixed_set(gact, G):
+    rng = np.random.default_rng(G)
+    specs = []
+    sizes = [0, 1, 100, 2048, 8192, 8193, 30000, 128 * 1000, 128 * 1024, 0, 70001, 197 * 197 * 4]
+    for k, n in enumerate(sizes):
+        x = syn.draw_numpy(syn.NORMAL if k % 2 else syn.RELU, n, 50 + k) if n else np.empty(0, np.float32)
+        if k % 3 == 0:
+            x = syn.f32_to_bf16_bits(x) if n else np.empty(0, np.uint16)
+        specs.append((x, int(rng.choice([1, 2, 4, 8])), int(rng.integers(0, 2**63))))
+    multi_case(gact, specs, G)
+
+
+def test_multi_tensor_many_small(gact):
+    rng = np.random.default_rng(0)
+    specs = [(syn.f32_to_bf16_bits(syn.draw_numpy(syn.NORMAL, int(rng.integers(1, 6000)), k)),
+              int(rng.choice([1, 2, 4, 8])), k) for k in range(400)]
+    multi_case(gact, specs, 128)
+
+
+# ------------------------------------------------------ allocator feeds multi
+def test_allocator_bits_drive_a_multi_launch(gact):
+    L = 24
+    c = syn.lognormal_sensitivities(L, 2999)
+    ns = [int(v) for v in np.random.default_rng(1).integers(1, 40, L) * 256]
+    bits = gact.gact_allocate_bits(c, ns, 2.0)
+    assert np.array_equal(bits, oracle.allocate_bits(c, ns, 2.0))
+    specs = [(syn.draw_numpy(syn.RELU, ns[l], 2000 + l), int(bits[l]), l) for l in range(L)]
+    multi_case(gact, specs, 256)
