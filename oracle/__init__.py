@@ -49,6 +49,8 @@ def lib() -> ctypes.CDLL:
         vp = ctypes.c_void_p
         L.gact_oracle_philox4x32_10.argtypes = [vp, vp, vp]
         L.gact_oracle_philox4x32_10.restype = None
+        L.gact_oracle_threads.argtypes = []
+        L.gact_oracle_threads.restype = i32
         L.gact_oracle_noise.argtypes = [u64, u64]
         L.gact_oracle_noise.restype = ctypes.c_float
         L.gact_oracle_num_groups.argtypes = [i64, i32]
@@ -88,6 +90,10 @@ def philox4x32_10(ctr, key) -> np.ndarray:
     out = np.empty(4, dtype=np.uint32)
     lib().gact_oracle_philox4x32_10(_ptr(c), _ptr(k), _ptr(out))
     return out
+
+
+def threads() -> int:
+    return int(lib().gact_oracle_threads())
 
 
 def noise(seed: int, i: int) -> float:

@@ -36,9 +36,23 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 #define GACT_ORACLE_F32 0
 #define GACT_ORACLE_BF16 1
+
+/* threads the group / element loops run on (groups are independent and the
+   noise is a function of the index, so threading cannot change a result) */
+int gact_oracle_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------ Philox */
 /*
