@@ -26,6 +26,9 @@ gact::Geometry make_geometry(int group_size) {
     geo.lpg = group_size / kPerLane;
     geo.lanes_used = (64 / geo.lpg) * geo.lpg;
     geo.pow2 = (geo.lpg & (geo.lpg - 1)) == 0 ? 1 : 0;
+    geo.lpg_shift = 0;
+    while ((1 << (geo.lpg_shift + 1)) <= geo.lpg) ++geo.lpg_shift;
+    geo.groups_per_tile = geo.lanes_used / geo.lpg;
     geo.group_size = group_size;
     return geo;
 }

@@ -32,6 +32,8 @@ struct Geometry {
     int32_t lpg;           // lanes per group, 1..32
     int32_t lanes_used;    // (64 / lpg) * lpg
     int32_t pow2;          // lpg is a power of two (DPP reductions, full tiles)
+    int32_t lpg_shift;     // log2(lpg) when pow2
+    int32_t groups_per_tile;
     int32_t group_size;
 };
 

@@ -59,10 +59,10 @@ __device__ __forceinline__ float lane_read(float v, int src_lane) {
         float, __builtin_amdgcn_ds_bpermute(src_lane << 2, __builtin_bit_cast(int, v)));
 }
 
-// min / max of finite values; written as compare+select so that the result
-// for (+0, -0) pairs is one of the inputs and no canonicalisation is inserted.
-__device__ __forceinline__ float fmin2(float a, float b) { return b < a ? b : a; }
-__device__ __forceinline__ float fmax2(float a, float b) { return b > a ? b : a; }
+// min / max of finite values (v_min_f32 / v_min3_f32).  The sign of a zero
+// result is not defined by these; the stored minimum is canonicalised later.
+__device__ __forceinline__ float fmin2(float a, float b) { return __builtin_fminf(a, b); }
+__device__ __forceinline__ float fmax2(float a, float b) { return __builtin_fmaxf(a, b); }
 
 // All lanes of a group (lpg neighbouring lanes, lpg a power of two <= 32,
 // groups aligned to lpg) end up with the group's min and max.
@@ -96,8 +96,9 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     for (int r = 0; r < 10; ++r) {
         const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
         const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        // three-input xor in one v_bitop3_b32 (truth table 0x96)
+        const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+        const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
@@ -174,11 +175,12 @@ __device__ __forceinline__ void load_tile_to_lds(const void* __restrict__ x, int
     }
 }
 
-// fp32 -> bf16 bits, round to nearest even (finite inputs; NaN stays NaN).
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-    uint32_t u = __builtin_bit_cast(uint32_t, f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x0040u;
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+// two fp32 -> two bf16 (low half = a), round to nearest even: v_cvt_pk_bf16_f32
+typedef float  f2v  __attribute__((ext_vector_type(2)));
+typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t bf16_pair_rne(float a, float b) {
+    const f2v v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf2v));
 }
 
 // LDS rows -> coalesced global stores of the dequantised tile.
@@ -209,17 +211,17 @@ __device__ __forceinline__ void store_tile_from_lds(void* __restrict__ y, int64_
             const float* row = lds + (e >> 5) * kRowDwords + (e & 31);
             const f4 a = *(const f4*)(row);
             const f4 b = *(const f4*)(row + 4);
-            uint32_t h[8] = {bf16_rne(a.x), bf16_rne(a.y), bf16_rne(a.z), bf16_rne(a.w),
-                             bf16_rne(b.x), bf16_rne(b.y), bf16_rne(b.z), bf16_rne(b.w)};
-            if (!EDGE || e + 8 <= ne) {
-                u4 t = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
-                        h[6] | (h[7] << 16)};
-                if (!EDGE) __builtin_nontemporal_store(t, (u4*)(p + e));
-                else *(u4*)(p + e) = t;
+            const u4 t = {bf16_pair_rne(a.x, a.y), bf16_pair_rne(a.z, a.w),
+                          bf16_pair_rne(b.x, b.y), bf16_pair_rne(b.z, b.w)};
+            if (!EDGE) {
+                __builtin_nontemporal_store(t, (u4*)(p + e));
+            } else if (e + 8 <= ne) {
+                *(u4*)(p + e) = t;
             } else {
+                const uint32_t h[4] = {t.x, t.y, t.z, t.w};
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    if (e + j < ne) p[e + j] = (uint16_t)h[j];
+                    if (e + j < ne) p[e + j] = (uint16_t)(h[j >> 1] >> (16 * (j & 1)));
             }
         }
     }
@@ -286,25 +288,26 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
     if (range >= 0x1p-100f) { inv = Bf / range; step = range / Bf; }
 
     const bool lane_live = !EDGE || my0 < ne;
-    const int grp_in_tile = lane / geo.lpg;
+    const int grp_in_tile = EDGE ? lane / geo.lpg : lane >> geo.lpg_shift;
     if (lane_live && lane == grp_in_tile * geo.lpg) {
-        const int64_t g = tile * (int64_t)(geo.lanes_used / geo.lpg) + grp_in_tile;
+        const int64_t g = tile * (int64_t)geo.groups_per_tile + grp_in_tile;
         t.gmin[g] = mn;
         t.gscale[g] = step;
     }
 
-    // stochastic rounding + packing: 8 elements per Philox block
+    // stochastic rounding + packing: 8 elements per Philox block.  Elements are
+    // visited last to first so that each word grows by one shift-or per code.
     uint32_t out[BITS];
 #pragma unroll
     for (int w = 0; w < BITS; ++w) out[w] = 0u;
     const uint64_t blk0 = (uint64_t)(e0 + my0) >> 3;
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
+    for (int c = 3; c >= 0; --c) {
         uint32_t r[4];
         const uint64_t blk = blk0 + (uint64_t)c;
         philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), t.seed_lo, t.seed_hi, r);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
+        for (int j = 7; j >= 0; --j) {
             const int e = c * 8 + j;
             const uint32_t r16 = (j & 1) ? (r[j >> 1] >> 16) : (r[j >> 1] & 0xFFFFu);
             // (r16 + 1/2) / 65536, exact in binary32 either way it is written
@@ -313,10 +316,13 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
             const float tt = d * inv;
             const float frac = __builtin_amdgcn_fractf(tt);      // tt - floor(tt), tt >= 0
             uint32_t q = (uint32_t)(int)tt + (u < frac ? 1u : 0u);
-            q = q < B ? q : B;
+            // tt <= B (1 + 2^-23): the fraction of an overshoot is below the
+            // smallest noise value 2^-17 unless B = 255, so only 8-bit codes
+            // can round past the top level
+            if (BITS == 8) q = q < B ? q : B;
             if (EDGE && my0 + e >= ne) q = 0u;
-            const int bit = e * BITS;
-            out[bit >> 5] |= q << (bit & 31);
+            const int w = (e * BITS) >> 5;
+            out[w] = (out[w] << BITS) | q;
         }
     }
 
@@ -391,7 +397,8 @@ __device__ __forceinline__ void decompress_tile(const TensorArgs& t, const Geome
                 in[w] = o.x; in[w + 1] = o.y; in[w + 2] = o.z; in[w + 3] = o.w;
             }
         }
-        const int64_t g = tile * (int64_t)(geo.lanes_used / geo.lpg) + lane / geo.lpg;
+        const int64_t g = tile * (int64_t)geo.groups_per_tile
+                          + (EDGE ? lane / geo.lpg : lane >> geo.lpg_shift);
         mn = t.gmin[g];
         step = t.gscale[g];
     }
