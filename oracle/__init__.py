@@ -53,6 +53,8 @@ def lib() -> ctypes.CDLL:
         L.gact_oracle_threads.restype = i32
         L.gact_oracle_noise.argtypes = [u64, u64]
         L.gact_oracle_noise.restype = ctypes.c_float
+        L.gact_oracle_noise_fill.argtypes = [u64, u64, i64, vp]
+        L.gact_oracle_noise_fill.restype = None
         L.gact_oracle_num_groups.argtypes = [i64, i32]
         L.gact_oracle_num_groups.restype = i64
         L.gact_oracle_packed_bytes.argtypes = [i64, i32]
@@ -145,7 +147,17 @@ def compress_with_noise(x: np.ndarray, group_size: int, bits: int, u: np.ndarray
 
 
 def noise_array(seed: int, n: int, start: int = 0) -> np.ndarray:
-    return np.array([noise(seed, start + i) for i in range(n)], dtype=np.float32)
+    """u for elements start .. start+n-1 under `seed`."""
+    u = np.empty(n, dtype=np.float32)
+    lib().gact_oracle_noise_fill(seed & (2**64 - 1), start, n, _ptr(u))
+    return u
+
+
+def compress_slice(x: np.ndarray, group_size: int, bits: int, seed: int, start: int):
+    """Oracle result for elements start .. start+len(x)-1 of a larger tensor;
+    `start` must be a multiple of the group size."""
+    assert start % group_size == 0
+    return compress_with_noise(x, group_size, bits, noise_array(seed, x.size, start))
 
 
 def decompress(packed: np.ndarray, gmin: np.ndarray, gscale: np.ndarray,

@@ -103,6 +103,13 @@ float gact_oracle_noise(uint64_t seed, uint64_t i)
     return ((float)r16 + 0.5f) * 0x1p-16f;
 }
 
+/* noise for elements start .. start+n-1 of a tensor (lets a test check a slice
+   of a large tensor: groups are independent once their noise is given) */
+void gact_oracle_noise_fill(uint64_t seed, uint64_t start, int64_t n, float *u)
+{
+    for (int64_t i = 0; i < n; ++i) u[i] = gact_oracle_noise(seed, start + (uint64_t)i);
+}
+
 /* ------------------------------------------------------------ bf16 <-> f32 */
 static float bf16_to_f32(uint16_t h)
 {
