@@ -30,6 +30,7 @@ gact::Geometry make_geometry(int group_size) {
     while ((1 << (geo.lpg_shift + 1)) <= geo.lpg) ++geo.lpg_shift;
     geo.groups_per_tile = geo.lanes_used / geo.lpg;
     geo.group_size = group_size;
+    geo.group_shift = geo.lpg_shift + 5;
     return geo;
 }
 
@@ -65,9 +66,17 @@ int make_args(bool compress, const void* x, void* packed, float* gmin, float* gs
     return GACT_OK;
 }
 
+// blocks a tensor needs: compress takes 4 wavefront tiles per block, decompress
+// a fixed span of elements per block
+int64_t blocks_for(bool compress, const gact::TensorArgs& t) {
+    if (compress) return (t.tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t span = gact::dec_block_elems(t.dtype, t.bits);
+    return (t.n + span - 1) / span;
+}
+
 int run_single(bool compress, const gact::TensorArgs& t, const gact::Geometry& geo, void* stream) {
     if (t.n == 0) return GACT_OK;
-    const int64_t blocks = (t.tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    const int64_t blocks = blocks_for(compress, t);
     if (blocks > 0x7FFFFFFFll) return GACT_E_ARG;
     return gact_launch_single(compress ? 1 : 0, &t, &geo, (unsigned)blocks, stream) == 0
                ? GACT_OK : GACT_E_HIP;
@@ -99,7 +108,7 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
         if (d.n == 0) continue;
         first.push_back((uint32_t)blocks);
         table.push_back(t);
-        blocks += (uint64_t)((t.tiles + kWavesPerBlock - 1) / kWavesPerBlock);
+        blocks += (uint64_t)blocks_for(compress, t);
         if (blocks > 0x7FFFFFFFull) return GACT_E_ARG;
     }
     const int live = (int)table.size();

@@ -18,7 +18,7 @@ struct TensorArgs {
     float*      gscale;    // per-group dequantisation step
     void*       y;         // decompress output
     int64_t     n;         // elements
-    int64_t     tiles;     // wavefront tiles covering the tensor
+    int64_t     tiles;     // compress: wavefront tiles covering the tensor (unused by decompress)
     int64_t     packed_words;  // gact_packed_bytes / 4
     uint32_t    seed_lo, seed_hi;
     int32_t     bits;
@@ -35,7 +35,21 @@ struct Geometry {
     int32_t lpg_shift;     // log2(lpg) when pow2
     int32_t groups_per_tile;
     int32_t group_size;
+    int32_t group_shift;   // log2(group_size) when pow2
 };
+
+// Decompress launch shape.  A unit is the 1 KB of output one coalesced
+// wavefront store covers (256 fp32 or 512 bf16 elements); a block of four
+// wavefronts takes 4 * units consecutive units.  Units per wavefront were
+// chosen by sweep on MI355X over the benchmark activation sets (% of HBM peak,
+// decompress): fp32 1/2/3/4/8 units -> 52/66/72/75/65, bf16 1/2/3/4 units ->
+// 60/79/69/70 (BERT-shaped) and 56/73/72/73 (ViT-shaped).
+constexpr int dec_units_per_wave(int dtype, int /*bits*/) {
+    return dtype == GACT_DT_F32 ? 4 : 2;
+}
+constexpr int dec_block_elems(int dtype, int bits) {
+    return 4 * dec_units_per_wave(dtype, bits) * (dtype == GACT_DT_F32 ? 256 : 512);
+}
 
 }  // namespace gact
 

@@ -5,23 +5,27 @@
 // the exact arithmetic contract is stated in include/gact.h.
 //
 // How the work is laid out
+//   Compress
 //   * One wavefront owns one "tile": 64 lanes x 32 consecutive elements
 //     (2048 elements when the group size is a power of two).  A group of G
 //     elements is G/32 neighbouring lanes, so group statistics are a handful
 //     of DPP steps and every lane does the two IEEE divisions of its group
 //     once per 32 elements.
-//   * HBM is always touched with fully coalesced 16-byte accesses (lane i of
-//     load k reads bytes [k*1024 + 16 i, +16)).  The switch between that
-//     layout and "32 consecutive elements per lane" goes through a private,
-//     padded LDS region per wavefront (row stride 36 dwords: conflict-free
-//     128-bit LDS reads and writes).
+//   * HBM is read with fully coalesced 16-byte loads (lane i of load k reads
+//     bytes [k*1024 + 16 i, +16)).  The switch from that layout to "32
+//     consecutive elements per lane" goes through a private, padded LDS region
+//     per wavefront (row stride 36 dwords: conflict-free 128-bit LDS reads and
+//     writes).
 //   * With 32 elements per lane a lane owns 32*bits packed bits = `bits`
 //     dwords, and neighbouring lanes own neighbouring dwords: the packed
-//     stream is written (and read back) coalesced without further staging.
+//     stream is written coalesced without further staging.
 //   * Rounding noise: one Philox4x32-10 block per 8 consecutive elements, so
 //     four blocks per lane; the stream depends on (seed, element index) only.
-//   * No MFMA: the path is a streaming codec, bound by HBM (fp32 input) or by
-//     plain VALU work (bf16 input), not a contraction.
+//   Decompress
+//   * No layout switch and no LDS: a lane produces one 16-byte piece of output
+//     per coalesced store and fetches that piece's codes with one small load.
+//   * No MFMA anywhere: the path is a streaming codec, bound by HBM (fp32) or
+//     by plain VALU work (bf16 compress), not a contraction.
 //
 // Tiles that are not full (the end of a tensor) and group sizes that are not a
 // power of two take the guarded `Edge` instantiation of the same code.
@@ -109,69 +113,106 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
 }
 
+// Instructions the compiler does not select on its own.
+// floor(x) as int32 in one instruction.
+__device__ __forceinline__ int32_t cvt_floor_i32(float x) {
+    int32_t r;
+    asm("v_cvt_flr_i32_f32 %0, %1" : "=v"(r) : "v"(x));
+    return r;
+}
+// 2 * (low / high 16 bits of w) + c
+__device__ __forceinline__ uint32_t mad2_lo16(uint32_t w, uint32_t c) {
+    uint32_t r;
+    asm("v_mad_u32_u16 %0, %1, 2, %2" : "=v"(r) : "v"(w), "v"(c));
+    return r;
+}
+__device__ __forceinline__ uint32_t mad2_hi16(uint32_t w, uint32_t c) {
+    uint32_t r;
+    asm("v_mad_u32_u16 %0, %1, 2, %2 op_sel:[1,0,0,0]" : "=v"(r) : "v"(w), "v"(c));
+    return r;
+}
+
 // ------------------------------------------------------- tile <-> HBM moves
-// Coalesced global -> LDS rows.  `ne` = number of valid elements of the tile
-// (2048 for a full tile).  Elements past `ne` are never read from memory.
+// The raw 16-byte loads of one tile: fp32 8 per lane, bf16 4 per lane.
+template <int DT>
+struct RawTile {
+    u4 r[DT == GACT_DT_F32 ? 8 : 4];
+};
+
+// Coalesced global loads.  `ne` = number of valid elements of the tile (2048
+// for a full tile); elements past `ne` are never read from memory and read 0.
 template <int DT, bool EDGE>
-__device__ __forceinline__ void load_tile_to_lds(const void* __restrict__ x, int64_t e0, int ne,
-                                                 float* __restrict__ lds, int lane) {
+__device__ __forceinline__ void load_tile(const void* __restrict__ x, int64_t e0, int ne, int lane,
+                                          RawTile<DT>& raw) {
     if (DT == GACT_DT_F32) {
-        const float* p = (const float*)x + e0;
-        f4 v[8];
+        const uint32_t* p = (const uint32_t*)x + e0;
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
             const int e = k * 256 + lane * 4;
             if (!EDGE) {
-                v[k] = __builtin_nontemporal_load((const f4*)(p + e));
+                raw.r[k] = __builtin_nontemporal_load((const u4*)(p + e));
             } else if (e + 4 <= ne) {
-                v[k] = *(const f4*)(p + e);
+                raw.r[k] = *(const u4*)(p + e);
             } else {
-                f4 t = {0.f, 0.f, 0.f, 0.f};
+                u4 t = {0u, 0u, 0u, 0u};
                 if (e + 0 < ne) t.x = p[e + 0];
                 if (e + 1 < ne) t.y = p[e + 1];
                 if (e + 2 < ne) t.z = p[e + 2];
-                v[k] = t;
+                raw.r[k] = t;
             }
-        }
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int e = k * 256 + lane * 4;
-            *(f4*)(lds + (e >> 5) * kRowDwords + (e & 31)) = v[k];
         }
     } else {
         const uint16_t* p = (const uint16_t*)x + e0;
-        u4 v[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int e = k * 512 + lane * 8;
             if (!EDGE) {
-                v[k] = __builtin_nontemporal_load((const u4*)(p + e));
+                raw.r[k] = __builtin_nontemporal_load((const u4*)(p + e));
             } else if (e + 8 <= ne) {
-                v[k] = *(const u4*)(p + e);
+                raw.r[k] = *(const u4*)(p + e);
             } else {
                 uint32_t h[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) h[j] = (e + j < ne) ? (uint32_t)p[e + j] : 0u;
                 u4 t = {h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16),
                         h[6] | (h[7] << 16)};
-                v[k] = t;
+                raw.r[k] = t;
             }
         }
+    }
+}
+
+// Raw tile -> LDS rows (row r = elements 32 r .. 32 r + 31), as fp32; bf16 is
+// widened here, exactly.
+template <int DT>
+__device__ __forceinline__ void stage_tile(const RawTile<DT>& raw, float* __restrict__ lds,
+                                           int lane) {
+    if (DT == GACT_DT_F32) {
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int e = k * 256 + lane * 4;
+            *(u4*)(lds + (e >> 5) * kRowDwords + (e & 31)) = raw.r[k];
+        }
+    } else {
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
             const int e = k * 512 + lane * 8;
+            const u4 w = raw.r[k];
             float* row = lds + (e >> 5) * kRowDwords + (e & 31);
-            f4 lo = {__builtin_bit_cast(float, v[k].x << 16),
-                     __builtin_bit_cast(float, v[k].x & 0xFFFF0000u),
-                     __builtin_bit_cast(float, v[k].y << 16),
-                     __builtin_bit_cast(float, v[k].y & 0xFFFF0000u)};
-            f4 hi = {__builtin_bit_cast(float, v[k].z << 16),
-                     __builtin_bit_cast(float, v[k].z & 0xFFFF0000u),
-                     __builtin_bit_cast(float, v[k].w << 16),
-                     __builtin_bit_cast(float, v[k].w & 0xFFFF0000u)};
-            *(f4*)(row) = lo;
-            *(f4*)(row + 4) = hi;
+            const u4 lo = {w.x << 16, w.x & 0xFFFF0000u, w.y << 16, w.y & 0xFFFF0000u};
+            const u4 hi = {w.z << 16, w.z & 0xFFFF0000u, w.w << 16, w.w & 0xFFFF0000u};
+            *(u4*)(row) = lo;
+            *(u4*)(row + 4) = hi;
         }
+    }
+}
+
+__device__ __forceinline__ void read_row(const float* __restrict__ lds, int row, float v[kPerLane]) {
+    const float* p = lds + row * kRowDwords;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const f4 q = *(const f4*)(p + 4 * k);
+        v[4 * k + 0] = q.x; v[4 * k + 1] = q.y; v[4 * k + 2] = q.z; v[4 * k + 3] = q.w;
     }
 }
 
@@ -181,50 +222,6 @@ typedef __bf16 bf2v __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t bf16_pair_rne(float a, float b) {
     const f2v v = {a, b};
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf2v));
-}
-
-// LDS rows -> coalesced global stores of the dequantised tile.
-template <int DT, bool EDGE>
-__device__ __forceinline__ void store_tile_from_lds(void* __restrict__ y, int64_t e0, int ne,
-                                                    const float* __restrict__ lds, int lane) {
-    if (DT == GACT_DT_F32) {
-        float* p = (float*)y + e0;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int e = k * 256 + lane * 4;
-            const f4 v = *(const f4*)(lds + (e >> 5) * kRowDwords + (e & 31));
-            if (!EDGE) {
-                __builtin_nontemporal_store(v, (f4*)(p + e));
-            } else if (e + 4 <= ne) {
-                *(f4*)(p + e) = v;
-            } else {
-                if (e + 0 < ne) p[e + 0] = v.x;
-                if (e + 1 < ne) p[e + 1] = v.y;
-                if (e + 2 < ne) p[e + 2] = v.z;
-            }
-        }
-    } else {
-        uint16_t* p = (uint16_t*)y + e0;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int e = k * 512 + lane * 8;
-            const float* row = lds + (e >> 5) * kRowDwords + (e & 31);
-            const f4 a = *(const f4*)(row);
-            const f4 b = *(const f4*)(row + 4);
-            const u4 t = {bf16_pair_rne(a.x, a.y), bf16_pair_rne(a.z, a.w),
-                          bf16_pair_rne(b.x, b.y), bf16_pair_rne(b.z, b.w)};
-            if (!EDGE) {
-                __builtin_nontemporal_store(t, (u4*)(p + e));
-            } else if (e + 8 <= ne) {
-                *(u4*)(p + e) = t;
-            } else {
-                const uint32_t h[4] = {t.x, t.y, t.z, t.w};
-#pragma unroll
-                for (int j = 0; j < 8; ++j)
-                    if (e + j < ne) p[e + j] = (uint16_t)(h[j >> 1] >> (16 * (j & 1)));
-            }
-        }
-    }
 }
 
 __device__ __forceinline__ void wave_lds_sync() {
@@ -251,18 +248,14 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
         ne = left < (int64_t)tile_elems ? (int)left : tile_elems;
     }
 
-    load_tile_to_lds<DT, EDGE>(t.x, e0, ne, lds, lane);
-    wave_lds_sync();
+    RawTile<DT> raw;
+    load_tile<DT, EDGE>(t.x, e0, ne, lane, raw);
 
+    // layout switch: coalesced rows in, 32 consecutive elements per lane out
     float v[kPerLane];
-    {
-        const float* row = lds + lane * kRowDwords;
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const f4 q = *(const f4*)(row + 4 * k);
-            v[4 * k + 0] = q.x; v[4 * k + 1] = q.y; v[4 * k + 2] = q.z; v[4 * k + 3] = q.w;
-        }
-    }
+    stage_tile<DT>(raw, lds, lane);
+    wave_lds_sync();
+    read_row(lds, lane, v);
 
     // group statistics
     const int my0 = lane * kPerLane;                 // first element of this lane in the tile
@@ -295,11 +288,21 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
         t.gscale[g] = step;
     }
 
-    // stochastic rounding + packing: 8 elements per Philox block.  Elements are
-    // visited last to first so that each word grows by one shift-or per code.
-    uint32_t out[BITS];
+    // stochastic rounding + packing: 8 elements per Philox block.
+    //
+    // The rule "q = floor(t) + [ (r+1/2)/2^16 < t - floor(t) ]" is evaluated in
+    // integers.  With T = 2^17 t (an exact rescaling of the binary32 product),
+    // C = ceil(T) and c = C mod 2^17:  round up  <=>  2 frac 2^16 > 2r + 1
+    // <=>  c >= 2r + 2  <=>  2r + 1 - C < -(floor(t) 2^17), hence
+    //     -q = (2r + 1 - C) >> 17   (arithmetic shift).
+    // C comes from one convert-with-floor of -T, 2r + (1 - C) from one 16-bit
+    // multiply-add that also selects the half word.  Codes are accumulated
+    // negated, last element first, one shift-add each; the word is negated at
+    // the end (two's complement: sum of (-q_j) << (j BITS) = -(packed word)).
+    uint32_t acc[BITS];
 #pragma unroll
-    for (int w = 0; w < BITS; ++w) out[w] = 0u;
+    for (int w = 0; w < BITS; ++w) acc[w] = 0u;
+    const float ninv17 = -(inv * 0x1p17f);
     const uint64_t blk0 = (uint64_t)(e0 + my0) >> 3;
 #pragma unroll
     for (int c = 3; c >= 0; --c) {
@@ -309,22 +312,23 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
 #pragma unroll
         for (int j = 7; j >= 0; --j) {
             const int e = c * 8 + j;
-            const uint32_t r16 = (j & 1) ? (r[j >> 1] >> 16) : (r[j >> 1] & 0xFFFFu);
-            // (r16 + 1/2) / 65536, exact in binary32 either way it is written
-            const float u = __builtin_fmaf((float)r16, 0x1p-16f, 0x1p-17f);
             const float d = v[e] - mn;
-            const float tt = d * inv;
-            const float frac = __builtin_amdgcn_fractf(tt);      // tt - floor(tt), tt >= 0
-            uint32_t q = (uint32_t)(int)tt + (u < frac ? 1u : 0u);
-            // tt <= B (1 + 2^-23): the fraction of an overshoot is below the
-            // smallest noise value 2^-17 unless B = 255, so only 8-bit codes
-            // can round past the top level
-            if (BITS == 8) q = q < B ? q : B;
-            if (EDGE && my0 + e >= ne) q = 0u;
+            const float tn = d * ninv17;                          // -T, T in [0, 2^25)
+            const uint32_t n1 = (uint32_t)(cvt_floor_i32(tn) + 1);  // 1 - C
+            const uint32_t y = (j & 1) ? mad2_hi16(r[j >> 1], n1) : mad2_lo16(r[j >> 1], n1);
+            int32_t nq = (int32_t)y >> 17;                        // -q
+            // t <= B (1 + 2^-23): an overshoot's fraction is below the smallest
+            // noise value 2^-17 unless B = 255, so only 8-bit codes can round
+            // past the top level
+            if (BITS == 8) nq = nq > -(int32_t)B ? nq : -(int32_t)B;
+            if (EDGE && my0 + e >= ne) nq = 0;
             const int w = (e * BITS) >> 5;
-            out[w] = (out[w] << BITS) | q;
+            acc[w] = (acc[w] << BITS) + (uint32_t)nq;
         }
     }
+    uint32_t out[BITS];
+#pragma unroll
+    for (int w = 0; w < BITS; ++w) out[w] = 0u - acc[w];
 
     // lane i owns dwords [i*BITS, (i+1)*BITS) of the tile's packed words
     const int64_t word0 = (e0 >> 5) * BITS + (int64_t)lane * BITS;
@@ -359,93 +363,137 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
 }
 
 // --------------------------------------------------------------- decompress
-template <int DT, int BITS, bool EDGE>
-__device__ __forceinline__ void decompress_tile(const TensorArgs& t, const Geometry& geo,
-                                                int64_t tile, float* __restrict__ lds, int lane) {
-    constexpr uint32_t B = (1u << BITS) - 1u;
-    const int tile_elems = geo.lanes_used * kPerLane;
-    const int64_t e0 = tile * (int64_t)tile_elems;
-    int ne = tile_elems;
-    if (EDGE) {
-        const int64_t left = t.n - e0;
-        ne = left < (int64_t)tile_elems ? (int)left : tile_elems;
-    }
-    const int my0 = lane * kPerLane;
-    const bool lane_live = !EDGE || (lane < geo.lanes_used && my0 < ne);
+// The decompressor needs no layout switch: a lane handles one 16-byte piece of
+// output (4 fp32 or 8 bf16 consecutive elements) per "unit", a unit being the
+// 1 KB that one coalesced wavefront store covers.  The piece's codes are
+// 4*BITS or 8*BITS consecutive bits of the packed string (a nibble, byte, half
+// word, word or two words), fetched with one small load; neighbouring lanes
+// fetch neighbouring bits, so those loads coalesce too.  The group's min and
+// step are two more loads that all lanes of a group share.  Wavefront w of a
+// block takes units w, w+4, w+8, ... so that the four wavefronts write one
+// contiguous 4 KB at each step.  Stores are the bottleneck here; the number of
+// units per wavefront (dec_units_per_wave) trades load latency hidden per
+// wavefront against the length of its store burst and was chosen by sweep.
+template <int DT>
+struct DecGeom {
+    static constexpr int kPiece = DT == GACT_DT_F32 ? 4 : 8;      // elements per lane and unit
+    static constexpr int kUnit = 64 * kPiece;                     // elements per unit
+};
 
-    uint32_t in[BITS];
-    float mn = 0.0f, step = 0.0f;
-    const int64_t word0 = (e0 >> 5) * BITS + (int64_t)lane * BITS;
-    const uint32_t* pk = (const uint32_t*)t.packed + word0;
+// codes of one piece, first element in the low bits
+template <int DT, int BITS>
+struct PieceBits {
+    static constexpr int kBits = DecGeom<DT>::kPiece * BITS;      // 4 .. 64
+    uint32_t lo, hi;
+};
+
+template <int DT, int BITS, bool EDGE>
+__device__ __forceinline__ void load_piece(const TensorArgs& t, int64_t e, PieceBits<DT, BITS>& pb) {
+    constexpr int nb = PieceBits<DT, BITS>::kBits;
+    const uint8_t* base = (const uint8_t*)t.packed;
+    const int64_t bit = e * BITS;
+    const int64_t byte = bit >> 3;
+    pb.lo = 0u; pb.hi = 0u;
+    if (EDGE) {
+        // byte by byte, never past the end of the (16-byte rounded) buffer
+        const int64_t total = t.packed_words * 4;
 #pragma unroll
-    for (int w = 0; w < BITS; ++w) in[w] = 0u;
-    if (lane_live) {
-        if (EDGE) {
-            // a live lane's words may run past the 16-byte-rounded end of the buffer
+        for (int k = 0; k < (nb + 7) / 8; ++k) {
+            const uint32_t v = (byte + k < total) ? (uint32_t)base[byte + k] : 0u;
+            if (k < 4) pb.lo |= v << (8 * k); else pb.hi |= v << (8 * (k - 4));
+        }
+        if (nb == 4) pb.lo = (pb.lo >> (int)(bit & 7)) & 0xFu;
+        return;
+    }
+    if (nb == 4) {
+        pb.lo = ((uint32_t)__builtin_nontemporal_load(base + byte) >> (int)(bit & 7)) & 0xFu;
+    } else if (nb == 8) {
+        pb.lo = __builtin_nontemporal_load(base + byte);
+    } else if (nb == 16) {
+        pb.lo = __builtin_nontemporal_load((const uint16_t*)(base + byte));
+    } else if (nb == 32) {
+        pb.lo = __builtin_nontemporal_load((const uint32_t*)(base + byte));
+    } else {
+        const u2 w = __builtin_nontemporal_load((const u2*)(base + byte));
+        pb.lo = w.x; pb.hi = w.y;
+    }
+}
+
+template <int DT, int BITS, bool EDGE, int UNITS>
+__device__ __forceinline__ void decompress_units(const TensorArgs& t, const Geometry& geo,
+                                                 int64_t block_in_tensor, int wave, int lane) {
+    constexpr uint32_t B = (1u << BITS) - 1u;
+    constexpr int P = DecGeom<DT>::kPiece;
+    constexpr int U = DecGeom<DT>::kUnit;
+    PieceBits<DT, BITS> pb[UNITS];
+    float mn[UNITS], step[UNITS];
+    int64_t e[UNITS];
 #pragma unroll
-            for (int w = 0; w < BITS; ++w)
-                if (word0 + w < t.packed_words) in[w] = pk[w];
-        } else if (BITS == 1) {
-            in[0] = __builtin_nontemporal_load(pk);
-        } else if (BITS == 2) {
-            const u2 o = __builtin_nontemporal_load((const u2*)pk);
-            in[0] = o.x; in[1] = o.y;
+    for (int k = 0; k < UNITS; ++k) {
+        const int64_t unit = block_in_tensor * (kWavesPerBlk * UNITS) + k * kWavesPerBlk + wave;
+        e[k] = unit * U + lane * P;
+        mn[k] = 0.0f; step[k] = 0.0f; pb[k].lo = 0u; pb[k].hi = 0u;
+        if (!EDGE || e[k] < t.n) {
+            load_piece<DT, BITS, EDGE>(t, e[k], pb[k]);
+            const int64_t g = geo.pow2 ? (e[k] >> geo.group_shift)
+                                       : (int64_t)((uint64_t)e[k] / (uint32_t)geo.group_size);
+            mn[k] = t.gmin[g];
+            step[k] = t.gscale[g];
+        }
+    }
+#pragma unroll
+    for (int k = 0; k < UNITS; ++k) {
+        if (EDGE && e[k] >= t.n) continue;
+        float o[P];
+#pragma unroll
+        for (int j = 0; j < P; ++j) {
+            const int bit = j * BITS;
+            const uint32_t q = ((bit < 32 ? pb[k].lo >> bit : pb[k].hi >> (bit - 32))) & B;
+            const float prod = (float)q * step[k];
+            o[j] = prod + mn[k];
+        }
+        if (DT == GACT_DT_F32) {
+            float* p = (float*)t.y + e[k];
+            if (!EDGE || e[k] + P <= t.n) {
+                const f4 v = {o[0], o[1], o[2], o[3]};
+                if (!EDGE) __builtin_nontemporal_store(v, (f4*)p); else *(f4*)p = v;
+            } else {
+#pragma unroll
+                for (int j = 0; j < P; ++j) if (e[k] + j < t.n) p[j] = o[j];
+            }
         } else {
+            uint16_t* p = (uint16_t*)t.y + e[k];
+            const u4 v = {bf16_pair_rne(o[0], o[1]), bf16_pair_rne(o[2 % P], o[3 % P]),
+                          bf16_pair_rne(o[4 % P], o[5 % P]), bf16_pair_rne(o[6 % P], o[7 % P])};
+            if (!EDGE || e[k] + P <= t.n) {
+                if (!EDGE) __builtin_nontemporal_store(v, (u4*)p); else *(u4*)p = v;
+            } else {
+                const uint32_t hh[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-            for (int w = 0; w < BITS; w += 4) {
-                const u4 o = __builtin_nontemporal_load((const u4*)(pk + w));
-                in[w] = o.x; in[w + 1] = o.y; in[w + 2] = o.z; in[w + 3] = o.w;
+                for (int j = 0; j < P; ++j)
+                    if (e[k] + j < t.n) p[j] = (uint16_t)(hh[j >> 1] >> (16 * (j & 1)));
             }
         }
-        const int64_t g = tile * (int64_t)geo.groups_per_tile
-                          + (EDGE ? lane / geo.lpg : lane >> geo.lpg_shift);
-        mn = t.gmin[g];
-        step = t.gscale[g];
     }
-
-    float* row = lds + lane * kRowDwords;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        float o[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int bit = (4 * k + j) * BITS;
-            const uint32_t q = (in[bit >> 5] >> (bit & 31)) & B;
-            const float prod = (float)q * step;
-            o[j] = prod + mn;
-        }
-        f4 ov = {o[0], o[1], o[2], o[3]};
-        *(f4*)(row + 4 * k) = ov;
-    }
-    wave_lds_sync();
-    store_tile_from_lds<DT, EDGE>(t.y, e0, ne, lds, lane);
 }
 
 // ------------------------------------------------------------------ kernels
-template <bool COMPRESS, bool EDGE>
-__device__ __forceinline__ void run_tile(const TensorArgs& t, const Geometry& geo, int64_t tile,
-                                         float* lds, int lane) {
-#define GACT_CASE(DT, BITS)                                                           \
-    if (COMPRESS) compress_tile<DT, BITS, EDGE>(t, geo, tile, lds, lane);             \
-    else decompress_tile<DT, BITS, EDGE>(t, geo, tile, lds, lane);                    \
-    break;
-    switch (t.dtype * 16 + t.bits) {
-        case GACT_DT_F32 * 16 + 1:  GACT_CASE(GACT_DT_F32, 1)
-        case GACT_DT_F32 * 16 + 2:  GACT_CASE(GACT_DT_F32, 2)
-        case GACT_DT_F32 * 16 + 4:  GACT_CASE(GACT_DT_F32, 4)
-        case GACT_DT_F32 * 16 + 8:  GACT_CASE(GACT_DT_F32, 8)
-        case GACT_DT_BF16 * 16 + 1: GACT_CASE(GACT_DT_BF16, 1)
-        case GACT_DT_BF16 * 16 + 2: GACT_CASE(GACT_DT_BF16, 2)
-        case GACT_DT_BF16 * 16 + 4: GACT_CASE(GACT_DT_BF16, 4)
-        case GACT_DT_BF16 * 16 + 8: GACT_CASE(GACT_DT_BF16, 8)
-        default: break;
+// uniform dispatch over (dtype, bits)
+#define GACT_DISPATCH(t, CALL)                                                       \
+    switch ((t).dtype * 16 + (t).bits) {                                             \
+        case GACT_DT_F32 * 16 + 1:  { CALL(GACT_DT_F32, 1) } break;                  \
+        case GACT_DT_F32 * 16 + 2:  { CALL(GACT_DT_F32, 2) } break;                  \
+        case GACT_DT_F32 * 16 + 4:  { CALL(GACT_DT_F32, 4) } break;                  \
+        case GACT_DT_F32 * 16 + 8:  { CALL(GACT_DT_F32, 8) } break;                  \
+        case GACT_DT_BF16 * 16 + 1: { CALL(GACT_DT_BF16, 1) } break;                 \
+        case GACT_DT_BF16 * 16 + 2: { CALL(GACT_DT_BF16, 2) } break;                 \
+        case GACT_DT_BF16 * 16 + 4: { CALL(GACT_DT_BF16, 4) } break;                 \
+        case GACT_DT_BF16 * 16 + 8: { CALL(GACT_DT_BF16, 8) } break;                 \
+        default: break;                                                              \
     }
-#undef GACT_CASE
-}
 
-template <bool COMPRESS>
-__device__ __forceinline__ void run_block(const TensorArgs& t, const Geometry& geo,
-                                          int64_t block_in_tensor) {
+__device__ __forceinline__ void compress_block(const TensorArgs& t, const Geometry& geo,
+                                               int64_t block_in_tensor) {
     __shared__ __attribute__((aligned(16))) float lds_all[kWavesPerBlk * kWaveLdsDw];
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
@@ -454,8 +502,33 @@ __device__ __forceinline__ void run_block(const TensorArgs& t, const Geometry& g
     if (tile >= t.tiles) return;
     // a tile is "full" when all its elements exist and G is a power of two
     const bool full = geo.pow2 && (tile + 1) * (int64_t)(geo.lanes_used * kPerLane) <= t.n;
-    if (full) run_tile<COMPRESS, false>(t, geo, tile, lds, lane);
-    else run_tile<COMPRESS, true>(t, geo, tile, lds, lane);
+#define GACT_C_FULL(DT, BITS) compress_tile<DT, BITS, false>(t, geo, tile, lds, lane);
+#define GACT_C_EDGE(DT, BITS) compress_tile<DT, BITS, true>(t, geo, tile, lds, lane);
+    if (full) { GACT_DISPATCH(t, GACT_C_FULL) } else { GACT_DISPATCH(t, GACT_C_EDGE) }
+#undef GACT_C_FULL
+#undef GACT_C_EDGE
+}
+
+__device__ __forceinline__ void decompress_block(const TensorArgs& t, const Geometry& geo,
+                                                 int64_t block_in_tensor) {
+    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    // full: every element of the block's span exists
+    const bool full = (block_in_tensor + 1) * (int64_t)dec_block_elems(t.dtype, t.bits) <= t.n;
+#define GACT_D_FULL(DT, BITS) \
+    decompress_units<DT, BITS, false, dec_units_per_wave(DT, BITS)>(t, geo, block_in_tensor, wave, lane);
+#define GACT_D_EDGE(DT, BITS) \
+    decompress_units<DT, BITS, true, dec_units_per_wave(DT, BITS)>(t, geo, block_in_tensor, wave, lane);
+    if (full) { GACT_DISPATCH(t, GACT_D_FULL) } else { GACT_DISPATCH(t, GACT_D_EDGE) }
+#undef GACT_D_FULL
+#undef GACT_D_EDGE
+}
+
+template <bool COMPRESS>
+__device__ __forceinline__ void run_block(const TensorArgs& t, const Geometry& geo,
+                                          int64_t block_in_tensor) {
+    if (COMPRESS) compress_block(t, geo, block_in_tensor);
+    else decompress_block(t, geo, block_in_tensor);
 }
 
 template <bool COMPRESS>
