@@ -112,11 +112,13 @@ int gact_decompress(const void *d_packed, const float *d_gmin,
  *                    compress reads x and writes packed/gmin/gscale (y unused);
  *                    decompress reads packed/gmin/gscale and writes y (x unused).
  *   d_workspace      device scratch of at least gact_multi_workspace_bytes(L)
- *                    bytes, 16-byte aligned; holds the launch table until the
- *                    enqueued kernel has run, so it must not be reused for a
- *                    different table before then.
- * The table is copied from a staging area the call owns for its duration with
- * a stream-ordered copy; h_descs may be reused as soon as the call returns.
+ *                    bytes, 16-byte aligned.  With more than 64 non-empty
+ *                    tensors it holds the launch table until the enqueued
+ *                    kernel has run, so it must not be reused for a different
+ *                    table before then; smaller tables travel in the kernel
+ *                    arguments and leave it untouched.
+ * A table in the workspace is uploaded with a stream-ordered copy from host
+ * memory the call owns; h_descs may be reused as soon as the call returns.
  * L == 0, or all n == 0, is GACT_OK and launches nothing.
  */
 typedef struct {

@@ -51,25 +51,26 @@ int make_args(bool compress, const void* x, void* packed, float* gmin, float* gs
         if (!aligned(io, 16) || !aligned(packed, 16) || !aligned(gmin, 4) || !aligned(gscale, 4))
             return GACT_E_ARG;
     }
-    out->x = x;
+    const int64_t tiles = tiles_for(n, geo);
+    if (tiles > 0xFFFFFFFFll) return GACT_E_ARG;
+    out->io = compress ? const_cast<void*>(x) : y;
     out->packed = packed;
     out->gmin = gmin;
     out->gscale = gscale;
-    out->y = y;
     out->n = n;
-    out->tiles = tiles_for(n, geo);
-    out->packed_words = (int64_t)(gact_packed_bytes(n, bits) / 4);
     out->seed_lo = (uint32_t)seed;
     out->seed_hi = (uint32_t)(seed >> 32);
-    out->bits = bits;
-    out->dtype = dtype;
+    out->tiles = (uint32_t)tiles;
+    out->bits = (uint8_t)bits;
+    out->dtype = (uint8_t)dtype;
+    out->pad[0] = out->pad[1] = 0;
     return GACT_OK;
 }
 
 // blocks a tensor needs: compress takes 4 wavefront tiles per block, decompress
 // a fixed span of elements per block
 int64_t blocks_for(bool compress, const gact::TensorArgs& t) {
-    if (compress) return (t.tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+    if (compress) return ((int64_t)t.tiles + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t span = gact::dec_block_elems(t.dtype, t.bits);
     return (t.n + span - 1) / span;
 }
@@ -118,6 +119,17 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
     if (!d_workspace || !aligned(d_workspace, 16) ||
         workspace_bytes < gact_multi_workspace_bytes(L))
         return GACT_E_ARG;
+
+    if (live <= gact::kInlineTensors) {
+        // small table: by value in the kernel arguments, nothing to upload
+        gact::InlineTable tab;
+        std::memset(&tab, 0, sizeof(tab));
+        std::memcpy(tab.t, table.data(), (size_t)live * sizeof(gact::TensorArgs));
+        std::memcpy(tab.first_block, first.data(), first.size() * sizeof(uint32_t));
+        tab.L = live;
+        return gact_launch_multi_inline(compress ? 1 : 0, &tab, &geo, (unsigned)blocks, stream) == 0
+                   ? GACT_OK : GACT_E_HIP;
+    }
 
     const size_t tb = table_bytes(live);
     std::vector<unsigned char> image(tb + first.size() * sizeof(uint32_t));

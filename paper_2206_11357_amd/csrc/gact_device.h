@@ -10,19 +10,18 @@
 
 namespace gact {
 
-// One tensor of a launch.  Pointers are device pointers.
+// One tensor of a launch (56 bytes).  Pointers are device pointers.
 struct TensorArgs {
-    const void* x;         // compress input
+    void*       io;        // compress: input x (read only); decompress: output y
     void*       packed;    // bit string (compress output, decompress input)
     float*      gmin;      // per-group minimum
     float*      gscale;    // per-group dequantisation step
-    void*       y;         // decompress output
     int64_t     n;         // elements
-    int64_t     tiles;     // compress: wavefront tiles covering the tensor (unused by decompress)
-    int64_t     packed_words;  // gact_packed_bytes / 4
     uint32_t    seed_lo, seed_hi;
-    int32_t     bits;
-    int32_t     dtype;
+    uint32_t    tiles;     // compress: wavefront tiles covering the tensor
+    uint8_t     bits;
+    uint8_t     dtype;
+    uint8_t     pad[2];
 };
 
 // How a group size maps onto a wavefront: a lane owns 32 consecutive
@@ -36,6 +35,14 @@ struct Geometry {
     int32_t groups_per_tile;
     int32_t group_size;
     int32_t group_shift;   // log2(group_size) when pow2
+};
+
+// A launch table small enough to travel in the kernel arguments (4 KB limit).
+constexpr int kInlineTensors = 64;
+struct InlineTable {
+    TensorArgs t[kInlineTensors];
+    uint32_t   first_block[kInlineTensors + 1];
+    int32_t    L;
 };
 
 // Decompress launch shape.  A unit is the 1 KB of output one coalesced
@@ -55,6 +62,8 @@ constexpr int dec_block_elems(int dtype, int bits) {
 
 extern "C" int gact_launch_single(int compress, const gact::TensorArgs* t,
                                   const gact::Geometry* geo, unsigned blocks, void* stream);
+extern "C" int gact_launch_multi_inline(int compress, const gact::InlineTable* tab,
+                                        const gact::Geometry* geo, unsigned blocks, void* stream);
 extern "C" int gact_launch_multi(int compress, const gact::TensorArgs* d_table,
                                  const uint32_t* d_first_block, int L,
                                  const gact::Geometry* geo, unsigned blocks, void* stream);

@@ -47,6 +47,11 @@ constexpr int kWaveLdsDw    = kLanes * kRowDwords;
 constexpr int kWavesPerBlk  = 4;
 constexpr int kBlockThreads = kLanes * kWavesPerBlk;
 
+// 32-bit words of the packed buffer: ceil(n*bits/8) bytes rounded up to 16
+__device__ __forceinline__ int64_t packed_words(const TensorArgs& t) {
+    return (int64_t)((((uint64_t)t.n * (uint64_t)t.bits + 127u) >> 7) << 2);
+}
+
 // ---------------------------------------------------------------- lane moves
 template <int CTRL>
 __device__ __forceinline__ float dpp(float v) {
@@ -249,7 +254,7 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
     }
 
     RawTile<DT> raw;
-    load_tile<DT, EDGE>(t.x, e0, ne, lane, raw);
+    load_tile<DT, EDGE>(t.io, e0, ne, lane, raw);
 
     // layout switch: coalesced rows in, 32 consecutive elements per lane out
     float v[kPerLane];
@@ -348,14 +353,14 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
         }
     } else {
         // the packed buffer ends at a multiple of 16 bytes; pad words are zero
-        const int64_t words_total = t.packed_words;
+        const int64_t words_total = packed_words(t);
 #pragma unroll
         for (int w = 0; w < BITS; ++w)
             if (lane < geo.lanes_used && word0 + w < words_total) pk[w] = out[w];
         // when a tile is narrower than 128*8/BITS elements' worth of padding
         // (group sizes that are not a power of two), up to three pad words lie
         // past the last tile's lanes: the last tile zeroes them
-        if (tile == t.tiles - 1 && lane < 4) {
+        if (tile == (int64_t)t.tiles - 1 && lane < 4) {
             const int64_t w = (e0 >> 5) * BITS + (int64_t)geo.lanes_used * BITS + lane;
             if (w < words_total) ((uint32_t*)t.packed)[w] = 0u;
         }
@@ -396,7 +401,7 @@ __device__ __forceinline__ void load_piece(const TensorArgs& t, int64_t e, Piece
     pb.lo = 0u; pb.hi = 0u;
     if (EDGE) {
         // byte by byte, never past the end of the (16-byte rounded) buffer
-        const int64_t total = t.packed_words * 4;
+        const int64_t total = packed_words(t) * 4;
 #pragma unroll
         for (int k = 0; k < (nb + 7) / 8; ++k) {
             const uint32_t v = (byte + k < total) ? (uint32_t)base[byte + k] : 0u;
@@ -453,7 +458,7 @@ __device__ __forceinline__ void decompress_units(const TensorArgs& t, const Geom
             o[j] = prod + mn[k];
         }
         if (DT == GACT_DT_F32) {
-            float* p = (float*)t.y + e[k];
+            float* p = (float*)t.io + e[k];
             if (!EDGE || e[k] + P <= t.n) {
                 const f4 v = {o[0], o[1], o[2], o[3]};
                 if (!EDGE) __builtin_nontemporal_store(v, (f4*)p); else *(f4*)p = v;
@@ -462,7 +467,7 @@ __device__ __forceinline__ void decompress_units(const TensorArgs& t, const Geom
                 for (int j = 0; j < P; ++j) if (e[k] + j < t.n) p[j] = o[j];
             }
         } else {
-            uint16_t* p = (uint16_t*)t.y + e[k];
+            uint16_t* p = (uint16_t*)t.io + e[k];
             const u4 v = {bf16_pair_rne(o[0], o[1]), bf16_pair_rne(o[2 % P], o[3 % P]),
                           bf16_pair_rne(o[4 % P], o[5 % P]), bf16_pair_rne(o[6 % P], o[7 % P])};
             if (!EDGE || e[k] + P <= t.n) {
@@ -499,7 +504,7 @@ __device__ __forceinline__ void compress_block(const TensorArgs& t, const Geomet
     const int lane = threadIdx.x & 63;
     float* lds = lds_all + wave * kWaveLdsDw;
     const int64_t tile = block_in_tensor * kWavesPerBlk + wave;
-    if (tile >= t.tiles) return;
+    if (tile >= (int64_t)t.tiles) return;
     // a tile is "full" when all its elements exist and G is a power of two
     const bool full = geo.pow2 && (tile + 1) * (int64_t)(geo.lanes_used * kPerLane) <= t.n;
 #define GACT_C_FULL(DT, BITS) compress_tile<DT, BITS, false>(t, geo, tile, lds, lane);
@@ -537,19 +542,34 @@ __global__ __launch_bounds__(kBlockThreads) void single_kernel(TensorArgs t, Geo
 }
 
 // Multi-tensor: block b belongs to the tensor l with first_block[l] <= b <
-// first_block[l+1]; the table sits in the caller's workspace.
-template <bool COMPRESS>
-__global__ __launch_bounds__(kBlockThreads) void multi_kernel(const TensorArgs* __restrict__ table,
-                                                              const uint32_t* __restrict__ first_block,
-                                                              int L, Geometry geo) {
-    const uint32_t b = blockIdx.x;
+// first_block[l+1].
+__device__ __forceinline__ int find_tensor(const uint32_t* first_block, int L, uint32_t b) {
     int lo = 0, hi = L;                 // invariant: first_block[lo] <= b < first_block[hi]
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (first_block[mid] <= b) lo = mid; else hi = mid;
     }
-    const TensorArgs t = table[lo];
-    run_block<COMPRESS>(t, geo, (int64_t)(b - first_block[lo]));
+    return lo;
+}
+
+// Table in device memory (the caller's workspace): any number of tensors.
+template <bool COMPRESS>
+__global__ __launch_bounds__(kBlockThreads) void multi_kernel(const TensorArgs* __restrict__ table,
+                                                              const uint32_t* __restrict__ first_block,
+                                                              int L, Geometry geo) {
+    const uint32_t b = blockIdx.x;
+    const int l = find_tensor(first_block, L, b);
+    const TensorArgs t = table[l];
+    run_block<COMPRESS>(t, geo, (int64_t)(b - first_block[l]));
+}
+
+// Table passed by value in the kernel arguments: up to kInlineTensors tensors,
+// no upload and no host synchronisation before the launch.
+template <bool COMPRESS>
+__global__ __launch_bounds__(kBlockThreads) void multi_inline_kernel(InlineTable tab, Geometry geo) {
+    const uint32_t b = blockIdx.x;
+    const int l = find_tensor(tab.first_block, tab.L, b);
+    run_block<COMPRESS>(tab.t[l], geo, (int64_t)(b - tab.first_block[l]));
 }
 
 }  // namespace gact
@@ -562,6 +582,18 @@ extern "C" int gact_launch_single(int compress, const gact::TensorArgs* t, const
         hipLaunchKernelGGL(gact::single_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), 0, s, *t, *geo);
     else
         hipLaunchKernelGGL(gact::single_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), 0, s, *t, *geo);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+extern "C" int gact_launch_multi_inline(int compress, const gact::InlineTable* tab,
+                                        const gact::Geometry* geo, unsigned blocks, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    if (compress)
+        hipLaunchKernelGGL(gact::multi_inline_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), 0, s,
+                           *tab, *geo);
+    else
+        hipLaunchKernelGGL(gact::multi_inline_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), 0, s,
+                           *tab, *geo);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

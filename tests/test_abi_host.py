@@ -36,7 +36,7 @@ def test_size_helpers_match_the_oracle():
             assert gact.gact_num_groups(n, G) == oracle.num_groups(n, G)
     assert gact.gact_packed_bytes(-1, 2) == 0 and gact.gact_num_groups(-1, 32) == 0
     assert gact.gact_multi_workspace_bytes(0) == 0
-    assert gact.gact_multi_workspace_bytes(400) >= 400 * 80 + 401 * 4
+    assert gact.gact_multi_workspace_bytes(400) >= 400 * 56 + 401 * 4
 
 
 def test_argument_errors_are_reported_before_any_launch():
