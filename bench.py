@@ -181,7 +181,8 @@ def main() -> int:
                        "elements_per_s": round(n_total / d_avg * 1e3, 0),
                        "pct_hbm_peak": round(100 * alg_bytes / d_avg / 1e6 / HBM_PEAK_GBPS, 2)},
         "fused_pct_hbm_peak": round(100 * 2 * alg_bytes / (c_avg + d_avg) / 1e6 / HBM_PEAK_GBPS, 2),
-        "roofline": {"bound": "hbm", "kernel": "multi_kernel<compress>", "achieved": round(achieved, 1),
+        "roofline": {"bound": "hbm",
+                     "kernel": "gact::multi_inline_kernel<true>" if L <= 64 else "gact::multi_kernel<true>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic},
     }
