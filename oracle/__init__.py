@@ -69,6 +69,12 @@ def lib() -> ctypes.CDLL:
         L.gact_oracle_unpack_codes.restype = i32
         L.gact_oracle_allocate_bits.argtypes = [vp, vp, i32, ctypes.c_double, vp]
         L.gact_oracle_allocate_bits.restype = i32
+        L.gact_oracle_sensitivity.argtypes = [vp, vp, vp, vp, i32, i32, vp]
+        L.gact_oracle_sensitivity.restype = i32
+        L.gact_oracle_grad_stats_update.argtypes = [vp, vp, i64, i32, i64, vp, vp]
+        L.gact_oracle_grad_stats_update.restype = i32
+        L.gact_oracle_variance_ratio.argtypes = [vp, vp, i32, ctypes.c_double, vp]
+        L.gact_oracle_variance_ratio.restype = i32
         _lib = L
     return _lib
 
@@ -192,3 +198,44 @@ def allocate_bits(sensitivity, numel, avg_bit_budget: float) -> np.ndarray:
     if rc != 0:
         raise ValueError("gact_oracle_allocate_bits: rc=%d" % rc)
     return out
+
+
+def sensitivity(g0, g1, bits: int) -> float:
+    """Alg. 1's return value: 1/2 ||g0 - g1||^2 / S(bits) over lists of buffers
+    (float32 arrays, or uint16 arrays of bf16 bit patterns)."""
+    g0 = [np.ascontiguousarray(a).reshape(-1) for a in g0]
+    g1 = [np.ascontiguousarray(a).reshape(-1) for a in g1]
+    assert len(g0) == len(g1) and all(a.size == b.size and a.dtype == b.dtype for a, b in zip(g0, g1))
+    K = len(g0)
+    P0 = (ctypes.c_void_p * max(K, 1))(*[_ptr(a) for a in g0])
+    P1 = (ctypes.c_void_p * max(K, 1))(*[_ptr(a) for a in g1])
+    n = np.array([a.size for a in g0], dtype=np.int64)
+    dt = np.array([_dtype_of(a) for a in g0], dtype=np.int32)
+    out = ctypes.c_double(0.0)
+    rc = lib().gact_oracle_sensitivity(ctypes.addressof(P0), ctypes.addressof(P1), _ptr(n), _ptr(dt),
+                                       K, bits, ctypes.addressof(out))
+    if rc != 0:
+        raise ValueError("gact_oracle_sensitivity: bad argument")
+    return out.value
+
+
+def grad_stats_update(g: np.ndarray, mean: np.ndarray, t: int):
+    """In-place running-mean step; returns (sum g^2, sum mean_new^2)."""
+    g = np.ascontiguousarray(g).reshape(-1)
+    assert mean.dtype == np.float32 and mean.flags.c_contiguous and mean.size == g.size
+    a, b = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    rc = lib().gact_oracle_grad_stats_update(_ptr(g), _ptr(mean), g.size, _dtype_of(g), t,
+                                             ctypes.addressof(a), ctypes.addressof(b))
+    if rc != 0:
+        raise ValueError("gact_oracle_grad_stats_update: bad argument")
+    return a.value, b.value
+
+
+def variance_ratio(c, bits, grad_var: float) -> float:
+    c = np.ascontiguousarray(c, dtype=np.float32)
+    b = np.ascontiguousarray(bits, dtype=np.int32)
+    out = ctypes.c_double(0.0)
+    rc = lib().gact_oracle_variance_ratio(_ptr(c), _ptr(b), c.size, float(grad_var), ctypes.addressof(out))
+    if rc != 0:
+        raise ValueError("gact_oracle_variance_ratio: bad argument")
+    return out.value

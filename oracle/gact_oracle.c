@@ -327,3 +327,78 @@ int gact_oracle_allocate_bits(const float *sensitivity, const int64_t *numel,
     free(idx);
     return 0;
 }
+
+/* ------------------------------------------- sensitivity and variance alert */
+/*
+ * Alg. 1 (Sec. 4.2) returns, for tensor l, 1/2 ||g0 - g1||^2 / S(b_l), where
+ * g0 and g1 are the full gradients of two iterations that differ only in the
+ * seed of tensor l's compressor.  The gradient is a list of K parameter
+ * buffers; the norm runs over all of them.  Plain binary64 accumulation in
+ * index order.
+ */
+static double load_elem_f64(const void *x, int dtype, int64_t i)
+{
+    return (double)load_elem(x, dtype, i);
+}
+
+int gact_oracle_sensitivity(const void *const *g0, const void *const *g1,
+                            const int64_t *numel, const int *dtype, int K,
+                            int bits, double *out)
+{
+    if (K < 0 || !(bits == 1 || bits == 2 || bits == 4 || bits == 8)) return -1;
+    double acc = 0.0;
+    for (int k = 0; k < K; ++k) {
+        if (numel[k] < 0) return -1;
+        for (int64_t i = 0; i < numel[k]; ++i) {
+            double d = load_elem_f64(g0[k], dtype[k], i) - load_elem_f64(g1[k], dtype[k], i);
+            acc += d * d;
+        }
+    }
+    double B = (double)((1 << bits) - 1);
+    *out = 0.5 * acc * (B * B);          /* dividing by S(b) = (2^b-1)^-2 */
+    return 0;
+}
+
+/*
+ * Running mean of the gradient (Sec. 4.2: "the overall gradient variance can
+ * be computed by maintaining a running mean of the gradient").  Step t >= 1:
+ *   mean <- mean + (g - mean) * rt,   rt = (float)(1 / t) rounded once,
+ * each operation in binary32.  Returns sum g^2 and sum mean_new^2 in binary64.
+ */
+int gact_oracle_grad_stats_update(const void *g, float *mean, int64_t n,
+                                  int dtype, int64_t t, double *sum_g2,
+                                  double *sum_m2)
+{
+    if (n < 0 || t < 1) return -1;
+    const float rt = (float)(1.0 / (double)t);
+    double a = 0.0, b = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        float gi = load_elem(g, dtype, i);
+        float d = gi - mean[i];
+        float s = d * rt;
+        float m = mean[i] + s;
+        mean[i] = m;
+        a += (double)gi * (double)gi;
+        b += (double)m * (double)m;
+    }
+    *sum_g2 += a;
+    *sum_m2 += b;
+    return 0;
+}
+
+/* V(b) = sum_l c_l S(b_l) (Thm. 2, Eq. (var-decomposition)) over the gradient
+   variance; the caller alerts when the ratio exceeds its threshold. */
+int gact_oracle_variance_ratio(const float *c, const int32_t *bits, int L,
+                               double grad_var, double *ratio)
+{
+    double V = 0.0;
+    for (int l = 0; l < L; ++l) {
+        int b = bits[l];
+        if (!(b == 1 || b == 2 || b == 4 || b == 8) || !(c[l] >= 0.0f)) return -1;
+        double B = (double)((1 << b) - 1);
+        V += (double)c[l] / (B * B);
+    }
+    if (!(grad_var > 0.0)) return -1;
+    *ratio = V / grad_var;
+    return 0;
+}
