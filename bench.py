@@ -45,7 +45,8 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="resnet50_b64", choices=sorted(WORKLOADS))
+    ap.add_argument("--workload", default="resnet50_b64",
+                    choices=sorted(WORKLOADS) + ["grad_sensitivity"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=800_000_000)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -78,6 +79,9 @@ def main() -> int:
                           "read_bytes_per_launch": src.numel() * 4,
                           "write_bytes_per_launch": dst.numel() * 4, "launches": 5}))
         return 0
+
+    if args.workload == "grad_sensitivity":
+        return bench_grad_sensitivity(args, gact, torch, np, dev)
 
     builder, G, avg_bits, sens_seed, desc = WORKLOADS[args.workload]
     specs = getattr(syn, builder)()
@@ -216,6 +220,64 @@ def main() -> int:
                       % (len(take), acc, sample_bytes / 1e9, t1 - t0, t2 - t1),
         }
     print(json.dumps(out))
+    return 0
+
+
+def bench_grad_sensitivity(args, gact, torch, np, dev) -> int:
+    """Alg. 1's reduction 1/2 ||g0 - g1||^2 / S(b) and one running-statistics step
+    over a BERT-large-shaped fp32 gradient (391 buffers, 302 M parameters)."""
+    shapes = []
+    for _ in range(24):
+        shapes += [1024 * 1024] * 4 + [1024 * 4096] * 2 + [1024] * 6 + [4096]
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    g0 = [torch.randn(n, device=dev, generator=gen) for n in shapes]
+    g1 = [a + 0.01 * torch.randn(n, device=dev, generator=gen) for a, n in zip(g0, shapes)]
+    mean = [torch.zeros(n, device=dev) for n in shapes]
+    total = sum(shapes)
+    ws = torch.empty(gact.gact_reduce_workspace_bytes(len(shapes), total), dtype=torch.uint8, device=dev)
+    out1 = torch.empty(1, dtype=torch.float64, device=dev)
+    out2 = torch.empty(2, dtype=torch.float64, device=dev)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    pairs = gact.make_grad_pairs(g0, g1)          # marshalled once, outside the timed region
+    stats = gact.make_grad_stats(g0, mean)
+    for _ in range(args.warmup):
+        gact.gact_sensitivity(g0, g1, 2, out=out1, workspace=ws, pairs=pairs)
+        gact.gact_grad_stats_update(g0, mean, 1, out=out2, workspace=ws, stats=stats)
+    torch.cuda.synchronize()
+    s_ms, u_ms = [], []
+    t0 = time.perf_counter()
+    marks = []
+    for k in range(args.steps):
+        e0, e1, e2 = ev(), ev(), ev()
+        e0.record()
+        gact.gact_sensitivity(g0, g1, 2, out=out1, workspace=ws, pairs=pairs)
+        e1.record()
+        gact.gact_grad_stats_update(g0, mean, k + 2, out=out2, workspace=ws, stats=stats)
+        e2.record()
+        marks.append((e0, e1, e2))
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    for e0, e1, e2 in marks:
+        s_ms.append(e0.elapsed_time(e1))
+        u_ms.append(e1.elapsed_time(e2))
+    s_avg, u_avg = float(np.mean(s_ms)), float(np.mean(u_ms))
+    s_bytes, u_bytes = 8 * total, 12 * total        # two reads; two reads + one write
+    print(json.dumps({
+        "metric": "sensitivity reduction GB/s (bytes read), 1xMI355X", "value": round(s_bytes / s_avg / 1e6, 1),
+        "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(wall * 1e3 / args.steps, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f64 accumulation of f32 inputs", "data": "synthetic",
+        "config": {"workload": "grad_sensitivity", "buffers": len(shapes), "elements": total,
+                   "description": "BERT-large-shaped fp32 gradient pair; Alg. 1 reduction, then one running-mean step"},
+        "sensitivity": {"ms": round(s_avg, 4), "GBps": round(s_bytes / s_avg / 1e6, 1),
+                        "pct_hbm_peak": round(100 * s_bytes / s_avg / 1e6 / HBM_PEAK_GBPS, 2)},
+        "grad_stats_update": {"ms": round(u_avg, 4), "GBps": round(u_bytes / u_avg / 1e6, 1),
+                              "pct_hbm_peak": round(100 * u_bytes / u_avg / 1e6 / HBM_PEAK_GBPS, 2)},
+        "roofline": {"bound": "hbm", "kernel": "gact::diff_sq_kernel", "achieved": round(s_bytes / s_avg / 1e6, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(s_bytes / s_avg / 1e6 / HBM_PEAK_GBPS, 4),
+                     "traffic": None},
+    }))
     return 0
 
 

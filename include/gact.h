@@ -142,6 +142,61 @@ int gact_decompress_multi(const gact_tensor_desc *h_descs, int L, int group_size
                           void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Sensitivity of one context tensor (Alg. 1, Sec. 4.2).  g0 and g1 are the
+ * gradients of two iterations that differ only in the seed of tensor l's
+ * compressor, each a list of K parameter buffers; the call computes
+ *     c_l = 1/2 * sum_k ||g0_k - g1_k||^2 / S(bits),   S(b) = (2^b-1)^-2,
+ * `bits` being the width tensor l was compressed with, accumulated in binary64
+ * in a fixed order (the result does not depend on scheduling).
+ *   h_pairs      host array of K buffer pairs; device pointers inside, 16-byte
+ *                aligned, both buffers of a pair have n elements of `dtype`.
+ *   d_out        device double[1], receives c_l when the stream reaches it.
+ *   d_workspace  device scratch, >= gact_reduce_workspace_bytes(K, sum of n),
+ *                16-byte aligned; in use until the enqueued kernels have run.
+ * K == 0 or all n == 0 writes 0.
+ */
+typedef struct {
+    const void *g0;
+    const void *g1;
+    int64_t     n;
+    int32_t     dtype;     /* gact_dtype */
+    int32_t     reserved;
+} gact_grad_pair;
+
+size_t gact_reduce_workspace_bytes(int K, int64_t total_elems);
+
+int gact_sensitivity(const gact_grad_pair *h_pairs, int K, int bits, double *d_out,
+                     void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Running gradient statistics for the a-posteriori alert of Sec. 4.2 ("the
+ * overall gradient variance can be computed by maintaining a running mean of
+ * the gradient").  Step t >= 1 over K parameter buffers, binary32 per element:
+ *     mean <- mean + (g - mean) * rt,    rt = (float)(1 / t),
+ * and, in binary64, d_out[0] = sum g^2, d_out[1] = sum mean_new^2.  With the
+ * caller's running average s_t of d_out[0], Var[g] ~ s_t - d_out[1].
+ *   mean   device float[n] per buffer, read and written in place (start at 0).
+ */
+typedef struct {
+    const void *g;
+    float      *mean;
+    int64_t     n;
+    int32_t     dtype;     /* gact_dtype of g */
+    int32_t     reserved;
+} gact_grad_stat;
+
+int gact_grad_stats_update(const gact_grad_stat *h_stats, int K, int64_t t, double *d_out,
+                           void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Variance alert (host only): V(b) = sum_l c_l S(b_l) (Thm. 2) against the
+ * gradient variance.  Writes V / grad_var to *h_ratio (may be NULL) and
+ * returns 1 if it exceeds `threshold`, 0 if not, a negative code on error.
+ */
+int gact_variance_alert(const float *h_sensitivity, const int32_t *h_bits, int L,
+                        double grad_var, double threshold, double *h_ratio);
+
+/*
  * Bit allocator (host only, synchronous; Eq. (ilp), Sec. 4.1-4.2).
  *   h_sensitivity in  c_l >= 0, finite, L floats (Alg. 1's estimate)
  *   h_numel       in  D_l >= 0, L values

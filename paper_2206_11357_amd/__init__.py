@@ -30,7 +30,8 @@ GACT_E_HIP = -5
 EXPORTS = (
     "gact_num_groups", "gact_packed_bytes", "gact_error_string", "gact_compress",
     "gact_decompress", "gact_multi_workspace_bytes", "gact_compress_multi",
-    "gact_decompress_multi", "gact_allocate_bits",
+    "gact_decompress_multi", "gact_allocate_bits", "gact_reduce_workspace_bytes",
+    "gact_sensitivity", "gact_grad_stats_update", "gact_variance_alert",
 )
 
 
@@ -45,6 +46,18 @@ class TensorDesc(ctypes.Structure):
     _fields_ = [("x", ctypes.c_void_p), ("packed", ctypes.c_void_p), ("gmin", ctypes.c_void_p),
                 ("gscale", ctypes.c_void_p), ("y", ctypes.c_void_p), ("n", ctypes.c_int64),
                 ("seed", ctypes.c_uint64), ("bits", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+
+
+class GradPair(ctypes.Structure):
+    """Mirror of gact_grad_pair."""
+    _fields_ = [("g0", ctypes.c_void_p), ("g1", ctypes.c_void_p), ("n", ctypes.c_int64),
+                ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32)]
+
+
+class GradStat(ctypes.Structure):
+    """Mirror of gact_grad_stat."""
+    _fields_ = [("g", ctypes.c_void_p), ("mean", ctypes.c_void_p), ("n", ctypes.c_int64),
+                ("dtype", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -72,6 +85,14 @@ def _load() -> ctypes.CDLL:
     lib.gact_decompress_multi.restype = i32
     lib.gact_allocate_bits.argtypes = [vp, vp, i32, ctypes.c_double, vp]
     lib.gact_allocate_bits.restype = i32
+    lib.gact_reduce_workspace_bytes.argtypes = [i32, i64]
+    lib.gact_reduce_workspace_bytes.restype = sz
+    lib.gact_sensitivity.argtypes = [vp, i32, i32, vp, vp, sz, vp]
+    lib.gact_sensitivity.restype = i32
+    lib.gact_grad_stats_update.argtypes = [vp, i32, i64, vp, vp, sz, vp]
+    lib.gact_grad_stats_update.restype = i32
+    lib.gact_variance_alert.argtypes = [vp, vp, i32, ctypes.c_double, ctypes.c_double, vp]
+    lib.gact_variance_alert.restype = i32
     return lib
 
 
@@ -206,3 +227,92 @@ def gact_allocate_bits(sensitivity, numel, avg_bit_budget: float) -> np.ndarray:
     if rc != GACT_OK:
         raise GactError(rc, "gact_allocate_bits")
     return out
+
+
+# ------------------------------------------------- sensitivity and the alert
+def gact_reduce_workspace_bytes(K: int, total_elems: int) -> int:
+    return int(lib.gact_reduce_workspace_bytes(K, total_elems))
+
+
+def _reduce_workspace(tensors, workspace):
+    total = sum(int(t.numel()) for t in tensors)
+    need = gact_reduce_workspace_bytes(len(tensors), total)
+    if workspace is None:
+        dev = tensors[0].device if tensors else torch.device("cuda")
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+    return workspace
+
+
+def make_grad_pairs(g0: Sequence[torch.Tensor], g1: Sequence[torch.Tensor]):
+    """ctypes array of gact_grad_pair (reusable across calls while the buffers live)."""
+    K = len(g0)
+    if len(g1) != K:
+        raise ValueError("g0 and g1 must list the same buffers")
+    arr = (GradPair * max(K, 1))()
+    for k in range(K):
+        a, b = _flat(g0[k]), _flat(g1[k])
+        if a.numel() != b.numel() or a.dtype != b.dtype:
+            raise ValueError("buffer %d: g0 and g1 differ in size or dtype" % k)
+        arr[k].g0, arr[k].g1, arr[k].n, arr[k].dtype = a.data_ptr(), b.data_ptr(), a.numel(), dtype_code(a.dtype)
+    return arr
+
+
+def make_grad_stats(g: Sequence[torch.Tensor], mean: Sequence[torch.Tensor]):
+    """ctypes array of gact_grad_stat."""
+    K = len(g)
+    if len(mean) != K:
+        raise ValueError("g and mean must list the same buffers")
+    arr = (GradStat * max(K, 1))()
+    for k in range(K):
+        a, m = _flat(g[k]), _flat(mean[k])
+        if a.numel() != m.numel() or m.dtype != torch.float32:
+            raise ValueError("buffer %d: mean must be float32 of the gradient's size" % k)
+        arr[k].g, arr[k].mean, arr[k].n, arr[k].dtype = a.data_ptr(), m.data_ptr(), a.numel(), dtype_code(a.dtype)
+    return arr
+
+
+def gact_sensitivity(g0: Sequence[torch.Tensor], g1: Sequence[torch.Tensor], bits: int,
+                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                     stream=None, pairs=None) -> torch.Tensor:
+    """1/2 ||g0 - g1||^2 / S(bits) over lists of gradient buffers -> device float64[1].
+    `pairs` (from make_grad_pairs) skips re-marshalling the buffer list."""
+    K = len(g0)
+    arr = pairs if pairs is not None else make_grad_pairs(g0, g1)
+    workspace = _reduce_workspace(list(g0), workspace)
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=workspace.device)
+    rc = lib.gact_sensitivity(ctypes.addressof(arr), K, bits, out.data_ptr(), workspace.data_ptr(),
+                              workspace.numel(), _stream(stream))
+    if rc != GACT_OK:
+        raise GactError(rc, "gact_sensitivity")
+    return out
+
+
+def gact_grad_stats_update(g: Sequence[torch.Tensor], mean: Sequence[torch.Tensor], t: int,
+                           out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                           stream=None, stats=None) -> torch.Tensor:
+    """Running-mean step t over gradient buffers -> device float64[2] = (sum g^2, sum mean^2)."""
+    K = len(g)
+    arr = stats if stats is not None else make_grad_stats(g, mean)
+    workspace = _reduce_workspace(list(g), workspace)
+    if out is None:
+        out = torch.empty(2, dtype=torch.float64, device=workspace.device)
+    rc = lib.gact_grad_stats_update(ctypes.addressof(arr), K, t, out.data_ptr(), workspace.data_ptr(),
+                                    workspace.numel(), _stream(stream))
+    if rc != GACT_OK:
+        raise GactError(rc, "gact_grad_stats_update")
+    return out
+
+
+def gact_variance_alert(sensitivity, bits, grad_var: float, threshold: float):
+    """-> (alert: bool, V(b) / grad_var)"""
+    c = np.ascontiguousarray(sensitivity, dtype=np.float32)
+    b = np.ascontiguousarray(bits, dtype=np.int32)
+    if c.shape != b.shape or c.ndim != 1:
+        raise ValueError("sensitivity and bits must be 1-D and of equal length")
+    ratio = ctypes.c_double(0.0)
+    rc = lib.gact_variance_alert(c.ctypes.data, b.ctypes.data, c.size, float(grad_var),
+                                 float(threshold), ctypes.addressof(ratio))
+    if rc < 0:
+        raise GactError(rc, "gact_variance_alert")
+    return bool(rc), ratio.value

@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgact.so")
-SOURCES = [os.path.join(CSRC, "gact_kernels.hip"), os.path.join(CSRC, "gact_api.cpp")]
+SOURCES = [os.path.join(CSRC, "gact_kernels.hip"), os.path.join(CSRC, "gact_reduce.hip"),
+           os.path.join(CSRC, "gact_api.cpp")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -145,6 +145,49 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
                              stream) == 0 ? GACT_OK : GACT_E_HIP;
 }
 
+// ---------------------------------------------------------------- reductions
+size_t reduce_table_bytes(int K) {
+    return ((size_t)K * sizeof(gact::ReduceArgs) + (size_t)(K + 1) * sizeof(uint32_t) + 15) / 16 * 16;
+}
+
+// Builds and uploads the buffer table of a reduction launch.  On success
+// *blocks_out is the grid size, *d_partial the per-block result area behind
+// the table; returns 1 when there is nothing to reduce.
+int stage_reduction(const std::vector<gact::ReduceArgs>& bufs, void* d_workspace,
+                    size_t workspace_bytes, int nout, void* stream, unsigned* blocks_out,
+                    const gact::ReduceArgs** d_table, const uint32_t** d_first, double** d_partial) {
+    std::vector<gact::ReduceArgs> live;
+    std::vector<uint32_t> first;
+    uint64_t blocks = 0;
+    for (const gact::ReduceArgs& r : bufs) {
+        if (r.n == 0) continue;
+        const int64_t chunk = gact::reduce_chunk_elems(r.dtype);
+        first.push_back((uint32_t)blocks);
+        live.push_back(r);
+        blocks += (uint64_t)((r.n + chunk - 1) / chunk);
+        if (blocks > 0x7FFFFFFFull) return GACT_E_ARG;
+    }
+    first.push_back((uint32_t)blocks);
+    const int K = (int)live.size();
+    if (K == 0) return 1;
+    const size_t tb = reduce_table_bytes(K);
+    const size_t need = tb + (size_t)nout * blocks * sizeof(double);
+    if (!d_workspace || !aligned(d_workspace, 16) || workspace_bytes < need) return GACT_E_ARG;
+    std::vector<unsigned char> image(tb);
+    std::memcpy(image.data(), live.data(), (size_t)K * sizeof(gact::ReduceArgs));
+    std::memcpy(image.data() + (size_t)K * sizeof(gact::ReduceArgs), first.data(),
+                first.size() * sizeof(uint32_t));
+    // pageable source: the runtime has taken its own copy when this returns
+    if (hipMemcpyAsync(d_workspace, image.data(), image.size(), hipMemcpyHostToDevice,
+                       (hipStream_t)stream) != hipSuccess)
+        return GACT_E_HIP;
+    *blocks_out = (unsigned)blocks;
+    *d_table = (const gact::ReduceArgs*)d_workspace;
+    *d_first = (const uint32_t*)((const unsigned char*)d_workspace + (size_t)K * sizeof(gact::ReduceArgs));
+    *d_partial = (double*)((unsigned char*)d_workspace + tb);
+    return GACT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -210,6 +253,81 @@ int gact_compress_multi(const gact_tensor_desc* h_descs, int L, int group_size, 
 int gact_decompress_multi(const gact_tensor_desc* h_descs, int L, int group_size,
                           void* d_workspace, size_t workspace_bytes, void* stream) {
     return run_multi(false, h_descs, L, group_size, d_workspace, workspace_bytes, stream);
+}
+
+// -------------------------------------------------- sensitivity, statistics
+size_t gact_reduce_workspace_bytes(int K, int64_t total_elems) {
+    if (K < 0 || total_elems < 0) return 0;
+    // every buffer rounds up to whole 4096-element chunks; two results per block
+    const uint64_t blocks = (uint64_t)total_elems / 4096 + (uint64_t)K + 1;
+    return reduce_table_bytes(K) + (size_t)(2 * blocks * sizeof(double)) + 16;
+}
+
+int gact_sensitivity(const gact_grad_pair* h_pairs, int K, int bits, double* d_out,
+                     void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (!bits_ok(bits)) return GACT_E_BITS;
+    if (K < 0 || !d_out || !aligned(d_out, 8) || (K > 0 && !h_pairs)) return GACT_E_ARG;
+    std::vector<gact::ReduceArgs> bufs;
+    for (int k = 0; k < K; ++k) {
+        const gact_grad_pair& p = h_pairs[k];
+        if (p.n < 0 || !dtype_ok(p.dtype)) return GACT_E_ARG;
+        if (p.n > 0 && (!p.g0 || !p.g1 || !aligned(p.g0, 16) || !aligned(p.g1, 16))) return GACT_E_ARG;
+        bufs.push_back(gact::ReduceArgs{p.g0, const_cast<void*>(p.g1), p.n, p.dtype, 0});
+    }
+    unsigned blocks = 0;
+    const gact::ReduceArgs* d_table = nullptr;
+    const uint32_t* d_first = nullptr;
+    double* d_partial = nullptr;
+    const int rc = stage_reduction(bufs, d_workspace, workspace_bytes, 1, stream, &blocks, &d_table,
+                                   &d_first, &d_partial);
+    if (rc < 0) return rc;
+    if (rc == 1)     // nothing to reduce: the result is zero
+        return gact_launch_zero(d_out, 1, stream) == 0 ? GACT_OK : GACT_E_HIP;
+    const double B = (double)((1 << bits) - 1);
+    const int live = (int)(((const unsigned char*)d_first - (const unsigned char*)d_table) /
+                           sizeof(gact::ReduceArgs));
+    return gact_launch_diff_sq(d_table, d_first, live, blocks, d_partial, 0.5 * B * B, d_out,
+                               stream) == 0 ? GACT_OK : GACT_E_HIP;
+}
+
+int gact_grad_stats_update(const gact_grad_stat* h_stats, int K, int64_t t, double* d_out,
+                           void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (K < 0 || t < 1 || !d_out || !aligned(d_out, 8) || (K > 0 && !h_stats)) return GACT_E_ARG;
+    std::vector<gact::ReduceArgs> bufs;
+    for (int k = 0; k < K; ++k) {
+        const gact_grad_stat& p = h_stats[k];
+        if (p.n < 0 || !dtype_ok(p.dtype)) return GACT_E_ARG;
+        if (p.n > 0 && (!p.g || !p.mean || !aligned(p.g, 16) || !aligned(p.mean, 16))) return GACT_E_ARG;
+        bufs.push_back(gact::ReduceArgs{p.g, p.mean, p.n, p.dtype, 0});
+    }
+    unsigned blocks = 0;
+    const gact::ReduceArgs* d_table = nullptr;
+    const uint32_t* d_first = nullptr;
+    double* d_partial = nullptr;
+    const int rc = stage_reduction(bufs, d_workspace, workspace_bytes, 2, stream, &blocks, &d_table,
+                                   &d_first, &d_partial);
+    if (rc < 0) return rc;
+    if (rc == 1) return gact_launch_zero(d_out, 2, stream) == 0 ? GACT_OK : GACT_E_HIP;
+    const int live = (int)(((const unsigned char*)d_first - (const unsigned char*)d_table) /
+                           sizeof(gact::ReduceArgs));
+    const float rt = (float)(1.0 / (double)t);
+    return gact_launch_grad_stats(d_table, d_first, live, rt, blocks, d_partial, d_out, stream) == 0
+               ? GACT_OK : GACT_E_HIP;
+}
+
+int gact_variance_alert(const float* h_sensitivity, const int32_t* h_bits, int L, double grad_var,
+                        double threshold, double* h_ratio) {
+    if (L < 0 || (L > 0 && (!h_sensitivity || !h_bits)) || !(grad_var > 0.0)) return GACT_E_ARG;
+    double V = 0.0;
+    for (int l = 0; l < L; ++l) {
+        if (!bits_ok(h_bits[l])) return GACT_E_BITS;
+        if (!(h_sensitivity[l] >= 0.0f) || std::isinf(h_sensitivity[l])) return GACT_E_ARG;
+        const double B = (double)((1 << h_bits[l]) - 1);
+        V += (double)h_sensitivity[l] / (B * B);
+    }
+    const double ratio = V / grad_var;
+    if (h_ratio) *h_ratio = ratio;
+    return ratio > threshold ? 1 : 0;
 }
 
 // ---------------------------------------------------------------- allocator

@@ -45,6 +45,18 @@ struct InlineTable {
     int32_t    L;
 };
 
+// One buffer pair of a reduction launch: sensitivity reads a and b; gradient
+// statistics read a (the gradient) and read-modify-write b (the fp32 mean).
+struct ReduceArgs {
+    const void* a;
+    void*       b;
+    int64_t     n;
+    int32_t     dtype;     // of a (and of b for sensitivity)
+    int32_t     pad;
+};
+// elements of one buffer a block covers: 256 threads x 4 pieces of 16 bytes
+constexpr int64_t reduce_chunk_elems(int dtype) { return dtype == GACT_DT_F32 ? 4096 : 8192; }
+
 // Decompress launch shape.  A unit is the 1 KB of output one coalesced
 // wavefront store covers (256 fp32 or 512 bf16 elements); a block of four
 // wavefronts takes 4 * units consecutive units.  Units per wavefront were
@@ -62,6 +74,13 @@ constexpr int dec_block_elems(int dtype, int bits) {
 
 extern "C" int gact_launch_single(int compress, const gact::TensorArgs* t,
                                   const gact::Geometry* geo, unsigned blocks, void* stream);
+extern "C" int gact_launch_diff_sq(const gact::ReduceArgs* d_table, const uint32_t* d_first, int K,
+                                   unsigned blocks, double* d_partial, double scale, double* d_out,
+                                   void* stream);
+extern "C" int gact_launch_zero(double* d_out, int nout, void* stream);
+extern "C" int gact_launch_grad_stats(const gact::ReduceArgs* d_table, const uint32_t* d_first, int K,
+                                      float rt, unsigned blocks, double* d_partial, double* d_out,
+                                      void* stream);
 extern "C" int gact_launch_multi_inline(int compress, const gact::InlineTable* tab,
                                         const gact::Geometry* geo, unsigned blocks, void* stream);
 extern "C" int gact_launch_multi(int compress, const gact::TensorArgs* d_table,

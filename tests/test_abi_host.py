@@ -118,3 +118,23 @@ def test_bit_allocator_on_the_large_mixed_set_and_its_errors():
         with pytest.raises(gact.GactError) as e:
             gact.gact_allocate_bits(cc, dd, avg)
         assert e.value.code == code
+
+
+def test_variance_alert_matches_the_oracle_and_reports_errors():
+    rng = np.random.default_rng(4)
+    for _ in range(50):
+        L = int(rng.integers(1, 40))
+        c = rng.lognormal(0, 2, L).astype(np.float32)
+        bits = rng.choice([1, 2, 4, 8], L).astype(np.int32)
+        gv = float(rng.uniform(0.1, 100))
+        alert, ratio = gact.gact_variance_alert(c, bits, gv, 1.0)
+        want = oracle.variance_ratio(c, bits, gv)
+        assert ratio == pytest.approx(want, rel=1e-12) and alert == (want > 1.0)
+    assert gact.gact_variance_alert([], [], 1.0, 0.5) == (False, 0.0)
+    for c, b, gv, code in (([1.0], [3], 1.0, gact.GACT_E_BITS), ([-1.0], [2], 1.0, gact.GACT_E_ARG),
+                           ([1.0], [2], 0.0, gact.GACT_E_ARG), ([float("nan")], [2], 1.0, gact.GACT_E_ARG)):
+        with pytest.raises(gact.GactError) as e:
+            gact.gact_variance_alert(c, b, gv, 1.0)
+        assert e.value.code == code
+    assert gact.gact_reduce_workspace_bytes(0, 0) >= 16
+    assert gact.gact_reduce_workspace_bytes(3, 10000) >= 3 * 32 + 16 + 2 * 8 * (10000 // 4096 + 3)
