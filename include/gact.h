@@ -62,6 +62,10 @@ extern "C" {
 
 typedef enum { GACT_F32 = 0, GACT_BF16 = 1 } gact_dtype;
 
+/* Bit width that means "leave this tensor uncompressed" in the allocator's
+ * level sets and in multi-tensor descriptors. */
+#define GACT_BITS_UNCOMPRESSED 32
+
 enum {
     GACT_OK       =  0,
     GACT_E_ARG    = -1,  /* null pointer, n < 0, misaligned pointer, bad dtype, L < 0,
@@ -119,6 +123,8 @@ int gact_decompress(const void *d_packed, const float *d_gmin,
  *                    arguments and leave it untouched.
  * A table in the workspace is uploaded with a stream-ordered copy from host
  * memory the call owns; h_descs may be reused as soon as the call returns.
+ * A descriptor with bits == GACT_BITS_UNCOMPRESSED is skipped by both calls:
+ * the allocator left that tensor at full precision and the caller keeps it.
  * L == 0, or all n == 0, is GACT_OK and launches nothing.
  */
 typedef struct {
@@ -209,6 +215,18 @@ int gact_variance_alert(const float *h_sensitivity, const int32_t *h_bits, int L
  */
 int gact_allocate_bits(const float *h_sensitivity, const int64_t *h_numel, int L,
                        double avg_bit_budget, int32_t *h_bits_out);
+
+/*
+ * The same program over a caller-given level set: h_levels is strictly
+ * ascending and drawn from {1, 2, 4, 8, GACT_BITS_UNCOMPRESSED}; the descent
+ * starts from the top level and avg_bit_budget must be >= the lowest.  With 32
+ * in the set the most sensitive tensors can stay uncompressed, as in the
+ * paper's experiments (Sec. 6.1), S(32) = (2^32-1)^-2.
+ * gact_allocate_bits is this call with levels {1, 2, 4, 8}.
+ */
+int gact_allocate_bits_levels(const float *h_sensitivity, const int64_t *h_numel, int L,
+                              double avg_bit_budget, const int32_t *h_levels, int n_levels,
+                              int32_t *h_bits_out);
 
 #ifdef __cplusplus
 }

@@ -69,6 +69,8 @@ def lib() -> ctypes.CDLL:
         L.gact_oracle_unpack_codes.restype = i32
         L.gact_oracle_allocate_bits.argtypes = [vp, vp, i32, ctypes.c_double, vp]
         L.gact_oracle_allocate_bits.restype = i32
+        L.gact_oracle_allocate_bits_levels.argtypes = [vp, vp, i32, ctypes.c_double, vp, i32, vp]
+        L.gact_oracle_allocate_bits_levels.restype = i32
         L.gact_oracle_sensitivity.argtypes = [vp, vp, vp, vp, i32, i32, vp]
         L.gact_oracle_sensitivity.restype = i32
         L.gact_oracle_grad_stats_update.argtypes = [vp, vp, i64, i32, i64, vp, vp]
@@ -186,6 +188,19 @@ def unpack_codes(packed: np.ndarray, n: int, bits: int) -> np.ndarray:
     if rc != 0:
         raise ValueError("gact_oracle_unpack_codes: bad argument")
     return codes
+
+
+def allocate_bits_levels(sensitivity, numel, avg_bit_budget: float, levels) -> np.ndarray:
+    c = np.ascontiguousarray(sensitivity, dtype=np.float32)
+    d = np.ascontiguousarray(numel, dtype=np.int64)
+    lv = np.ascontiguousarray(levels, dtype=np.int32)
+    assert c.shape == d.shape and c.ndim == 1
+    out = np.empty(c.size, dtype=np.int32)
+    rc = lib().gact_oracle_allocate_bits_levels(_ptr(c), _ptr(d), c.size, float(avg_bit_budget),
+                                                _ptr(lv), lv.size, _ptr(out))
+    if rc != 0:
+        raise ValueError("gact_oracle_allocate_bits_levels: rc=%d" % rc)
+    return out
 
 
 def allocate_bits(sensitivity, numel, avg_bit_budget: float) -> np.ndarray:

@@ -284,17 +284,26 @@ int gact_oracle_unpack_codes(const uint8_t *packed, int64_t n, int bits,
  * per step.  budget = floor(avg * sum D).  Returns 0, -1 bad argument,
  * -4 if avg < 1 (no feasible scheme).
  */
-int gact_oracle_allocate_bits(const float *sensitivity, const int64_t *numel,
-                              int L, double avg_bit_budget, int32_t *bits_out)
+/* Same greedy descent over a caller-given ascending level set drawn from
+ * {1,2,4,8,32}; 32 means "leave the tensor uncompressed" (the paper keeps up
+ * to 32 bits for the most sensitive tensors, Sec. 6.1), S(32) = (2^32-1)^-2.
+ * Starts from the top level; -4 if avg is below the lowest level. */
+int gact_oracle_allocate_bits_levels(const float *sensitivity, const int64_t *numel,
+                                     int L, double avg_bit_budget,
+                                     const int32_t *level, int n_levels,
+                                     int32_t *bits_out)
 {
-    static const int level[4] = { 1, 2, 4, 8 };
-    if (L < 0) return -1;
-    if (!(avg_bit_budget >= 1.0)) return -4;
-    double S[9] = { 0 };
-    for (int k = 0; k < 4; ++k) {
-        double B = (double)((1 << level[k]) - 1);
-        S[level[k]] = 1.0 / (B * B);
+    if (L < 0 || n_levels < 1 || n_levels > 5) return -1;
+    double S[5];
+    for (int k = 0; k < n_levels; ++k) {
+        int b = level[k];
+        if (!(b == 1 || b == 2 || b == 4 || b == 8 || b == 32)) return -1;
+        if (k > 0 && level[k] <= level[k - 1]) return -1;
+        double B = ldexp(1.0, b) - 1.0;          /* 2^b - 1 */
+        S[k] = 1.0 / (B * B);
     }
+    if (!(avg_bit_budget >= (double)level[0])) return -4;
+    const int top = n_levels - 1;
     uint64_t total = 0;
     for (int l = 0; l < L; ++l) {
         double c = (double)sensitivity[l];
@@ -303,10 +312,10 @@ int gact_oracle_allocate_bits(const float *sensitivity, const int64_t *numel,
     }
     int *idx = (int *)malloc(sizeof(int) * (size_t)(L > 0 ? L : 1));
     if (!idx) return -1;
-    for (int l = 0; l < L; ++l) { idx[l] = 3; bits_out[l] = 8; }
+    for (int l = 0; l < L; ++l) { idx[l] = top; bits_out[l] = level[top]; }
     double cap = floor(avg_bit_budget * (double)total);
     uint64_t budget = (cap >= 18446744073709549568.0) ? UINT64_MAX : (uint64_t)cap;
-    uint64_t used = 8u * total;
+    uint64_t used = (uint64_t)level[top] * total;
 
     while (used > budget) {
         int best = -1;
@@ -314,11 +323,11 @@ int gact_oracle_allocate_bits(const float *sensitivity, const int64_t *numel,
         for (int l = 0; l < L; ++l) {
             if (numel[l] == 0 || idx[l] == 0) continue;
             int hi = level[idx[l]], lo = level[idx[l] - 1];
-            double key = ((double)sensitivity[l] * (S[lo] - S[hi]))
+            double key = ((double)sensitivity[l] * (S[idx[l] - 1] - S[idx[l]]))
                        / ((double)numel[l] * (double)(hi - lo));
             if (best < 0 || key < best_key) { best = l; best_key = key; }
         }
-        if (best < 0) break;                     /* cannot happen when avg >= 1 */
+        if (best < 0) break;                     /* cannot happen when avg >= lowest level */
         int hi = level[idx[best]], lo = level[idx[best] - 1];
         idx[best] -= 1;
         bits_out[best] = lo;
@@ -326,6 +335,14 @@ int gact_oracle_allocate_bits(const float *sensitivity, const int64_t *numel,
     }
     free(idx);
     return 0;
+}
+
+int gact_oracle_allocate_bits(const float *sensitivity, const int64_t *numel,
+                              int L, double avg_bit_budget, int32_t *bits_out)
+{
+    static const int32_t level[4] = { 1, 2, 4, 8 };
+    return gact_oracle_allocate_bits_levels(sensitivity, numel, L, avg_bit_budget,
+                                            level, 4, bits_out);
 }
 
 /* ------------------------------------------- sensitivity and variance alert */

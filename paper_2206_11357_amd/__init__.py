@@ -32,7 +32,9 @@ EXPORTS = (
     "gact_decompress", "gact_multi_workspace_bytes", "gact_compress_multi",
     "gact_decompress_multi", "gact_allocate_bits", "gact_reduce_workspace_bytes",
     "gact_sensitivity", "gact_grad_stats_update", "gact_variance_alert",
+    "gact_allocate_bits_levels",
 )
+GACT_BITS_UNCOMPRESSED = 32
 
 
 class GactError(RuntimeError):
@@ -85,6 +87,8 @@ def _load() -> ctypes.CDLL:
     lib.gact_decompress_multi.restype = i32
     lib.gact_allocate_bits.argtypes = [vp, vp, i32, ctypes.c_double, vp]
     lib.gact_allocate_bits.restype = i32
+    lib.gact_allocate_bits_levels.argtypes = [vp, vp, i32, ctypes.c_double, vp, i32, vp]
+    lib.gact_allocate_bits_levels.restype = i32
     lib.gact_reduce_workspace_bytes.argtypes = [i32, i64]
     lib.gact_reduce_workspace_bytes.restype = sz
     lib.gact_sensitivity.argtypes = [vp, i32, i32, vp, vp, sz, vp]
@@ -226,6 +230,21 @@ def gact_allocate_bits(sensitivity, numel, avg_bit_budget: float) -> np.ndarray:
                                 out.ctypes.data)
     if rc != GACT_OK:
         raise GactError(rc, "gact_allocate_bits")
+    return out
+
+
+def gact_allocate_bits_levels(sensitivity, numel, avg_bit_budget: float, levels) -> np.ndarray:
+    """Allocator over a level set drawn from {1, 2, 4, 8, 32}; 32 = leave uncompressed."""
+    c = np.ascontiguousarray(sensitivity, dtype=np.float32)
+    d = np.ascontiguousarray(numel, dtype=np.int64)
+    lv = np.ascontiguousarray(levels, dtype=np.int32)
+    if c.shape != d.shape or c.ndim != 1 or lv.ndim != 1:
+        raise ValueError("sensitivity and numel must be 1-D and of equal length")
+    out = np.empty(c.size, dtype=np.int32)
+    rc = lib.gact_allocate_bits_levels(c.ctypes.data, d.ctypes.data, c.size, float(avg_bit_budget),
+                                       lv.ctypes.data, lv.size, out.ctypes.data)
+    if rc != GACT_OK:
+        raise GactError(rc, "gact_allocate_bits_levels")
     return out
 
 

@@ -102,6 +102,10 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
     uint64_t blocks = 0;
     for (int l = 0; l < L; ++l) {
         const gact_tensor_desc& d = descs[l];
+        if (d.bits == GACT_BITS_UNCOMPRESSED) {          // left uncompressed by the allocator
+            if (d.n < 0) return GACT_E_ARG;
+            continue;
+        }
         gact::TensorArgs t;
         const int rc = make_args(compress, d.x, d.packed, d.gmin, d.gscale, d.y, d.n, d.seed,
                                  d.bits, d.dtype, geo, &t);
@@ -331,19 +335,25 @@ int gact_variance_alert(const float* h_sensitivity, const int32_t* h_bits, int L
 }
 
 // ---------------------------------------------------------------- allocator
-int gact_allocate_bits(const float* h_sensitivity, const int64_t* h_numel, int L,
-                       double avg_bit_budget, int32_t* h_bits_out) {
-    if (L < 0) return GACT_E_ARG;
-    if (!(avg_bit_budget >= 1.0)) return GACT_E_BUDGET;
+int gact_allocate_bits_levels(const float* h_sensitivity, const int64_t* h_numel, int L,
+                              double avg_bit_budget, const int32_t* h_levels, int n_levels,
+                              int32_t* h_bits_out) {
+    if (L < 0 || n_levels < 1 || n_levels > 5 || !h_levels) return GACT_E_ARG;
+    int level[5];
+    double S[5];
+    for (int k = 0; k < n_levels; ++k) {
+        const int b = h_levels[k];
+        if (!(bits_ok(b) || b == GACT_BITS_UNCOMPRESSED)) return GACT_E_BITS;
+        if (k > 0 && b <= level[k - 1]) return GACT_E_BITS;
+        level[k] = b;
+        const double B = std::ldexp(1.0, b) - 1.0;
+        S[k] = 1.0 / (B * B);
+    }
+    if (!(avg_bit_budget >= (double)level[0])) return GACT_E_BUDGET;
     if (L == 0) return GACT_OK;
     if (!h_sensitivity || !h_numel || !h_bits_out) return GACT_E_ARG;
 
-    static const int level[4] = {1, 2, 4, 8};
-    double S[4];
-    for (int k = 0; k < 4; ++k) {
-        const double B = (double)((1 << level[k]) - 1);
-        S[k] = 1.0 / (B * B);
-    }
+    const int top = n_levels - 1;
     uint64_t total = 0;
     for (int l = 0; l < L; ++l) {
         const double c = (double)h_sensitivity[l];
@@ -352,7 +362,7 @@ int gact_allocate_bits(const float* h_sensitivity, const int64_t* h_numel, int L
     }
     const double cap = std::floor(avg_bit_budget * (double)total);
     const uint64_t budget = cap >= 18446744073709549568.0 ? UINT64_MAX : (uint64_t)cap;
-    uint64_t used = 8u * total;
+    uint64_t used = (uint64_t)level[top] * total;
 
     // cost of moving tensor l from level index k to k-1: variance added per bit saved
     auto step_key = [&](int l, int k) {
@@ -365,11 +375,11 @@ int gact_allocate_bits(const float* h_sensitivity, const int64_t* h_numel, int L
             return a.key > b.key || (a.key == b.key && a.l > b.l);
         }
     };
-    std::vector<int> idx((size_t)L, 3);
+    std::vector<int> idx((size_t)L, top);
     std::priority_queue<Step, std::vector<Step>, Later> heap;
     for (int l = 0; l < L; ++l) {
-        h_bits_out[l] = 8;
-        if (h_numel[l] > 0) heap.push(Step{step_key(l, 3), l});
+        h_bits_out[l] = level[top];
+        if (h_numel[l] > 0 && top > 0) heap.push(Step{step_key(l, top), l});
     }
     while (used > budget && !heap.empty()) {
         const Step s = heap.top();
@@ -381,6 +391,13 @@ int gact_allocate_bits(const float* h_sensitivity, const int64_t* h_numel, int L
         if (k - 1 > 0) heap.push(Step{step_key(s.l, k - 1), s.l});
     }
     return GACT_OK;
+}
+
+int gact_allocate_bits(const float* h_sensitivity, const int64_t* h_numel, int L,
+                       double avg_bit_budget, int32_t* h_bits_out) {
+    static const int32_t levels[4] = {1, 2, 4, 8};
+    return gact_allocate_bits_levels(h_sensitivity, h_numel, L, avg_bit_budget, levels, 4,
+                                     h_bits_out);
 }
 
 }  // extern "C"

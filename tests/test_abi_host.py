@@ -138,3 +138,27 @@ def test_variance_alert_matches_the_oracle_and_reports_errors():
         assert e.value.code == code
     assert gact.gact_reduce_workspace_bytes(0, 0) >= 16
     assert gact.gact_reduce_workspace_bytes(3, 10000) >= 3 * 32 + 16 + 2 * 8 * (10000 // 4096 + 3)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_level_set_allocator_is_identical_to_the_oracle(seed):
+    rng = np.random.default_rng(1000 + seed)
+    L = int(rng.integers(0, 60))
+    levels = [(1, 2, 4, 8, 32), (2, 4, 8, 32), (4, 32), (1, 2, 4, 8), (8,), (1, 32)][seed % 6]
+    c = rng.lognormal(0, 3, L).astype(np.float32)
+    if L and seed % 3 == 0:
+        c[rng.integers(0, L, max(L // 3, 1))] = c[0]
+    D = (rng.integers(0, 4000, L) * 32).astype(np.int64)
+    avg = float(rng.uniform(levels[0], levels[-1] + 1))
+    got = gact.gact_allocate_bits_levels(c, D, avg, levels)
+    assert np.array_equal(got, oracle.allocate_bits_levels(c, D, avg, levels))
+
+
+def test_level_set_allocator_errors():
+    c, D = [1.0, 2.0], [64, 64]
+    for levels, avg, code in (((1, 3), 2.0, gact.GACT_E_BITS), ((2, 1), 2.0, gact.GACT_E_BITS),
+                              ((1, 2, 4, 8, 16), 2.0, gact.GACT_E_BITS), ((2, 4), 1.5, gact.GACT_E_BUDGET),
+                              ((), 2.0, gact.GACT_E_ARG)):
+        with pytest.raises(gact.GactError) as e:
+            gact.gact_allocate_bits_levels(c, D, avg, levels)
+        assert e.value.code == code

@@ -266,3 +266,37 @@ def test_allocator_bits_drive_a_multi_launch(gact):
     assert np.array_equal(bits, oracle.allocate_bits(c, ns, 2.0))
     specs = [(syn.draw_numpy(syn.RELU, ns[l], 2000 + l), int(bits[l]), l) for l in range(L)]
     multi_case(gact, specs, 256)
+
+
+def test_uncompressed_level_is_skipped_by_the_multi_calls(gact):
+    """bits = 32 in a descriptor: the allocator left the tensor at full
+    precision; neither call touches its buffers."""
+    L, G = 10, 256
+    c = syn.lognormal_sensitivities(L, 77)
+    c[3] = 1e9                                   # far more sensitive than the rest
+    ns = [int(v) * 256 for v in np.random.default_rng(2).integers(4, 60, L)]
+    avg = float((32 * ns[3] + 4 * (sum(ns) - ns[3])) / sum(ns))   # one tensor at 32, the rest at 4
+    bits = gact.gact_allocate_bits_levels(c, ns, avg, (1, 2, 4, 8, 32))
+    assert np.array_equal(bits, oracle.allocate_bits_levels(c, ns, avg, (1, 2, 4, 8, 32)))
+    assert bits[3] == 32 and np.all(np.delete(bits, 3) < 32)
+    x_np = [syn.draw_numpy(syn.NORMAL, ns[l], 300 + l) for l in range(L)]
+    xs = [torch.from_numpy(x).cuda() for x in x_np]
+    bufs = [gact.alloc_compressed(ns[l], G, 8, "cuda") for l in range(L)]
+    for p, mn, sc in bufs:
+        p.fill_(CANARY); mn.fill_(-7.0); sc.fill_(-7.0)
+    ys = [torch.full_like(x, -3.0) for x in xs]
+    descs = gact.make_descs(xs, [b[0] for b in bufs], [b[1] for b in bufs], [b[2] for b in bufs], ys,
+                            ns, bits, list(range(L)), [x.dtype for x in xs])
+    ws = torch.empty(gact.gact_multi_workspace_bytes(L), dtype=torch.uint8, device="cuda")
+    gact.gact_compress_multi(descs, L, G, ws)
+    gact.gact_decompress_multi(descs, L, G, ws)
+    torch.cuda.synchronize()
+    assert bool((bufs[3][0] == CANARY).all()) and bool((bufs[3][1] == -7.0).all())
+    assert bool((ys[3] == -3.0).all())
+    for l in range(L):
+        if l == 3:
+            continue
+        p_ref, mn_ref, sc_ref = oracle.compress(x_np[l], G, int(bits[l]), l)
+        nb = p_ref.size
+        assert np.array_equal(bufs[l][0][:nb].cpu().numpy(), p_ref)
+        assert np.array_equal(ys[l].cpu().numpy(), oracle.decompress(p_ref, mn_ref, sc_ref, ns[l], G, int(bits[l])))

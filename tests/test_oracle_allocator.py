@@ -124,3 +124,54 @@ def test_large_set_budget_and_cost_ordering():
     # cheapest further downgrade costs
     assert max(gain_up) <= min(loss_dn) * (1 + 1e-9)
     assert base > 0
+
+
+# ------------------------------------------------- level sets with pass-through
+def S32(b):
+    return 1.0 / (2.0 ** b - 1.0) ** 2
+
+
+def brute_force_levels(c, D, budget, levels):
+    best = None
+    for scheme in itertools.product(levels, repeat=len(c)):
+        if used(D, scheme) <= budget:
+            v = float(sum(float(ci) * S32(b) for ci, b in zip(c, scheme)))
+            if best is None or v < best:
+                best = v
+    return best
+
+
+@pytest.mark.parametrize("seed", range(25))
+def test_level_sets_with_an_uncompressed_level_are_optimal_for_their_cost(seed):
+    """Level 32 = tensor left uncompressed (the paper keeps up to 32 bits for
+    the most sensitive tensors, Sec. 6.1)."""
+    rng = np.random.default_rng(100 + seed)
+    L = int(rng.integers(1, 6))
+    levels = [(1, 2, 4, 8, 32), (2, 4, 8, 32), (4, 32), (1, 2, 4, 8), (8,)][seed % 5]
+    c = rng.lognormal(0, 3, L).astype(np.float32)
+    D = rng.integers(1, 50, L).astype(np.int64) * 32
+    avg = float(rng.uniform(levels[0], levels[-1]))
+    bits = oracle.allocate_bits_levels(c, D, avg, levels)
+    assert set(bits.tolist()) <= set(levels)
+    assert used(D, bits) <= int(np.floor(avg * D.sum()))
+    got = float(sum(float(ci) * S32(b) for ci, b in zip(c, bits)))
+    best = brute_force_levels(c, D, used(D, bits), levels)
+    assert got <= best * (1 + 1e-9) + 1e-30
+
+
+def test_level_set_special_cases():
+    c = np.array([1.0, 1e6, 1.0, 1.0], np.float32)
+    D = np.full(4, 1000, np.int64)
+    lv = (1, 2, 4, 8, 32)
+    assert oracle.allocate_bits_levels(c, D, 32.0, lv).tolist() == [32] * 4
+    assert oracle.allocate_bits_levels(c, D, 1.0, lv).tolist() == [1] * 4
+    # budget for one uncompressed tensor and 8 bits elsewhere: the sensitive one keeps 32
+    assert oracle.allocate_bits_levels(c, D, (32 + 3 * 8) / 4, lv).tolist() == [8, 32, 8, 8]
+    # the four-level set is the default allocator
+    rng = np.random.default_rng(9)
+    cc = rng.lognormal(0, 2, 30).astype(np.float32)
+    DD = rng.integers(1, 99, 30).astype(np.int64)
+    assert np.array_equal(oracle.allocate_bits_levels(cc, DD, 3.0, (1, 2, 4, 8)), oracle.allocate_bits(cc, DD, 3.0))
+    for lv_bad, avg in (((1, 3), 2.0), ((2, 1), 2.0), ((1, 1), 2.0), ((), 2.0), ((2, 4), 1.5), ((1, 2, 4, 8, 16), 2.0)):
+        with pytest.raises(ValueError):
+            oracle.allocate_bits_levels(cc, DD, avg, lv_bad)
