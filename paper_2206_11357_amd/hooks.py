@@ -1,0 +1,169 @@
+"""Saved-tensor hooks that route autograd's saved activations through the GACT
+compressor (arXiv 2206.11357, Sec. 5: one hook interface for all operators;
+Sec. 5.2: parameters and tensors that need no gradient are not quantized;
+Sec. 5.3: optional swap of the *compressed* tensors to host memory on side
+streams, with prefetch during the backward pass).
+
+This is glue around the library's kernels: ``pack`` calls ``gact_compress``,
+``unpack`` calls ``gact_decompress``.  Per-tensor bit widths and the
+replayable per-tensor seeds r_l of Alg. 1 come from the ``Controller``.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Callable, Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import (GACT_BITS_UNCOMPRESSED, alloc_compressed, gact_allocate_bits_levels,
+               gact_compress, gact_decompress, gact_sensitivity)
+
+
+@dataclass
+class _Packed:
+    index: int                 # position among the context tensors of this iteration
+    shape: torch.Size
+    dtype: torch.dtype
+    n: int
+    bits: int
+    packed: Optional[torch.Tensor]
+    gmin: Optional[torch.Tensor]
+    gscale: Optional[torch.Tensor]
+    host: Optional[tuple] = None          # pinned copies when swapped out
+    out_event: Optional[torch.cuda.Event] = None
+    in_event: Optional[torch.cuda.Event] = None
+
+
+class Controller:
+    """Holds the compression scheme b = (b_l), the seeds (r_l) and the
+    sensitivities c_l of the context tensors of one model."""
+
+    def __init__(self, params: Sequence[torch.Tensor] = (), group_size: int = 256, bits: int = 4,
+                 seed: int = 0, min_numel: int = 1024, swap: bool = False):
+        self.group_size = group_size
+        self.default_bits = bits
+        self.base_seed = seed
+        self.min_numel = min_numel
+        self.swap = swap
+        self.param_ptrs = {p.data_ptr() for p in params}
+        self.bits: Dict[int, int] = {}            # index l -> b_l
+        self.seed_override: Dict[int, int] = {}   # index l -> r_l (Alg. 1 reseeds one tensor)
+        self.numel: List[int] = []                # D_l seen in the last iteration
+        self.sensitivity: Optional[np.ndarray] = None
+        self._index = 0
+        self._live: Dict[int, _Packed] = {}
+        self._side = torch.cuda.Stream() if swap else None     # default priority
+
+    # ------------------------------------------------------------- iteration
+    def begin_iteration(self) -> None:
+        self._index = 0
+        self._live.clear()
+        self.numel = []
+
+    def seed_of(self, index: int) -> int:
+        return self.seed_override.get(index, self.base_seed * 1_000_003 + index)
+
+    def bits_of(self, index: int) -> int:
+        return self.bits.get(index, self.default_bits)
+
+    def _eligible(self, x: torch.Tensor) -> bool:
+        return (x.is_cuda and x.dtype in (torch.float32, torch.bfloat16) and x.numel() >= self.min_numel
+                and x.data_ptr() not in self.param_ptrs and x.is_contiguous())
+
+    # ------------------------------------------------------------------ hooks
+    def pack(self, x: torch.Tensor):
+        if not self._eligible(x):
+            return x
+        index = self._index
+        self._index += 1
+        self.numel.append(x.numel())
+        b = self.bits_of(index)
+        if b == GACT_BITS_UNCOMPRESSED:
+            return x
+        packed, gmin, gscale = gact_compress(x.detach(), self.group_size, b, self.seed_of(index))
+        h = _Packed(index, x.shape, x.dtype, x.numel(), b, packed, gmin, gscale)
+        if self.swap:
+            self._swap_out(h)
+        self._live[index] = h
+        return h
+
+    def unpack(self, h):
+        if not isinstance(h, _Packed):
+            return h
+        if h.host is not None:
+            self._swap_in(h)
+            nxt = self._live.get(h.index - 1)          # backward walks the tensors in reverse
+            if nxt is not None and nxt.host is not None and nxt.packed is None:
+                self._start_swap_in(nxt)
+            torch.cuda.current_stream().wait_event(h.in_event)
+        y = gact_decompress(h.packed, h.gmin, h.gscale, h.n, self.group_size, h.bits, dtype=h.dtype)
+        return y.view(h.shape)
+
+    def hooks(self):
+        """Context manager: ``with controller.hooks(): loss = model(x)``."""
+        return torch.autograd.graph.saved_tensors_hooks(self.pack, self.unpack)
+
+    # ------------------------------------------------------------------- swap
+    def _swap_out(self, h: _Packed) -> None:
+        done = torch.cuda.Event()
+        done.record()                                   # compression finished on the main stream
+        with torch.cuda.stream(self._side):
+            self._side.wait_event(done)
+            host = []
+            for t in (h.packed, h.gmin, h.gscale):
+                buf = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
+                buf.copy_(t, non_blocking=True)
+                t.record_stream(self._side)
+                host.append(buf)
+            h.out_event = torch.cuda.Event()
+            h.out_event.record()
+        h.host = tuple(host)
+        h.packed = h.gmin = h.gscale = None             # device copies may be reused once copied
+
+    def _start_swap_in(self, h: _Packed) -> None:
+        main = torch.cuda.current_stream()
+        with torch.cuda.stream(self._side):
+            self._side.wait_event(h.out_event)
+            dev = []
+            for buf in h.host:
+                t = torch.empty(buf.shape, dtype=buf.dtype, device="cuda")
+                t.copy_(buf, non_blocking=True)
+                t.record_stream(main)
+                dev.append(t)
+            h.in_event = torch.cuda.Event()
+            h.in_event.record()
+        h.packed, h.gmin, h.gscale = dev
+
+    def _swap_in(self, h: _Packed) -> None:
+        if h.packed is None:
+            self._start_swap_in(h)
+
+    # ------------------------------------------------------------ adaptation
+    def compute_sensitivities(self, fwdbwd: Callable[[], Sequence[torch.Tensor]]) -> np.ndarray:
+        """Alg. 1 for every context tensor.  ``fwdbwd`` runs one forward and
+        backward pass under ``self.hooks()`` on a fixed batch and returns the
+        gradient buffers.  L + 1 passes: one with the seeds (r_l), then one per
+        tensor with only that tensor's seed replaced by r_{L+1}."""
+        self.seed_override.clear()
+        self.begin_iteration()
+        g0 = [g.detach().clone() for g in fwdbwd()]
+        L = len(self.numel)
+        c = np.zeros(L, dtype=np.float32)
+        for l in range(L):
+            if self.bits_of(l) == GACT_BITS_UNCOMPRESSED:
+                continue
+            self.seed_override = {l: self.base_seed * 1_000_003 + L + 1_000_000}
+            self.begin_iteration()
+            g1 = fwdbwd()
+            c[l] = float(gact_sensitivity(g0, [g.detach() for g in g1], self.bits_of(l)).item())
+        self.seed_override.clear()
+        self.sensitivity = c
+        return c
+
+    def adapt(self, avg_bits: float, levels=(1, 2, 4, 8)) -> np.ndarray:
+        """Solve Eq. (ilp) for the sensitivities measured last."""
+        assert self.sensitivity is not None and len(self.numel) == len(self.sensitivity)
+        b = gact_allocate_bits_levels(self.sensitivity, self.numel, avg_bits, levels)
+        self.bits = {l: int(v) for l, v in enumerate(b)}
+        return b
