@@ -195,6 +195,18 @@ int gact_grad_stats_update(const gact_grad_stat *h_stats, int K, int64_t t, doub
                            void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Footprint of a tensor for duplicate detection (Sec. 5.2: a tensor saved by
+ * several operators is recognised by its data pointer, sampled points and its
+ * sum, and compressed once).  One read of the tensor:
+ *     d_out[0]     = sum of all elements, binary64, fixed order
+ *     d_out[1 + j] = element floor(j * n / n_samples), j < n_samples <= 32768
+ *   d_workspace  >= gact_reduce_workspace_bytes(1, n) bytes, 16-byte aligned.
+ * n == 0 writes zeros.
+ */
+int gact_footprint(const void *d_x, gact_dtype dtype, int64_t n, int n_samples, double *d_out,
+                   void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Variance alert (host only): V(b) = sum_l c_l S(b_l) (Thm. 2) against the
  * gradient variance.  Writes V / grad_var to *h_ratio (may be NULL) and
  * returns 1 if it exceeds `threshold`, 0 if not, a negative code on error.

@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.gact_oracle_allocate_bits.restype = i32
         L.gact_oracle_allocate_bits_levels.argtypes = [vp, vp, i32, ctypes.c_double, vp, i32, vp]
         L.gact_oracle_allocate_bits_levels.restype = i32
+        L.gact_oracle_footprint.argtypes = [vp, i64, i32, i32, vp]
+        L.gact_oracle_footprint.restype = i32
         L.gact_oracle_sensitivity.argtypes = [vp, vp, vp, vp, i32, i32, vp]
         L.gact_oracle_sensitivity.restype = i32
         L.gact_oracle_grad_stats_update.argtypes = [vp, vp, i64, i32, i64, vp, vp]
@@ -254,3 +256,13 @@ def variance_ratio(c, bits, grad_var: float) -> float:
     if rc != 0:
         raise ValueError("gact_oracle_variance_ratio: bad argument")
     return out.value
+
+
+def footprint(x: np.ndarray, n_samples: int) -> np.ndarray:
+    """[sum, x[floor(j n / n_samples)] for j < n_samples] as float64."""
+    x = np.ascontiguousarray(x).reshape(-1)
+    out = np.zeros(1 + n_samples, dtype=np.float64)
+    rc = lib().gact_oracle_footprint(_ptr(x), x.size, _dtype_of(x), n_samples, _ptr(out))
+    if rc != 0:
+        raise ValueError("gact_oracle_footprint: bad argument")
+    return out

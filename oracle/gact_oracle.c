@@ -432,3 +432,24 @@ int gact_oracle_variance_ratio(const float *c, const int32_t *bits, int L,
     *ratio = V / grad_var;
     return 0;
 }
+
+/* ---------------------------------------------------------------- footprint */
+/*
+ * Footprint for duplicate detection (Sec. 5.2: a tensor saved by several
+ * operators is recognised by its data pointer, sampled points and sum).
+ * out[0] = sum of all elements; out[1 + j] = element floor(j * n / n_samples),
+ * j < n_samples, widened to binary64.  The data pointer is the caller's part.
+ */
+int gact_oracle_footprint(const void *x, int64_t n, int dtype, int n_samples,
+                          double *out)
+{
+    if (n < 0 || n_samples < 0 || !(dtype == GACT_ORACLE_F32 || dtype == GACT_ORACLE_BF16)) return -1;
+    acc_t acc = { 0.0, 0.0 };
+    for (int64_t i = 0; i < n; ++i) acc_add(&acc, load_elem_f64(x, dtype, i));
+    out[0] = acc_value(&acc);
+    for (int j = 0; j < n_samples; ++j) {
+        int64_t i = n > 0 ? (int64_t)(((__int128)j * (__int128)n) / n_samples) : 0;
+        out[1 + j] = n > 0 ? load_elem_f64(x, dtype, i) : 0.0;
+    }
+    return 0;
+}

@@ -32,7 +32,7 @@ EXPORTS = (
     "gact_decompress", "gact_multi_workspace_bytes", "gact_compress_multi",
     "gact_decompress_multi", "gact_allocate_bits", "gact_reduce_workspace_bytes",
     "gact_sensitivity", "gact_grad_stats_update", "gact_variance_alert",
-    "gact_allocate_bits_levels",
+    "gact_allocate_bits_levels", "gact_footprint",
 )
 GACT_BITS_UNCOMPRESSED = 32
 
@@ -95,6 +95,8 @@ def _load() -> ctypes.CDLL:
     lib.gact_sensitivity.restype = i32
     lib.gact_grad_stats_update.argtypes = [vp, i32, i64, vp, vp, sz, vp]
     lib.gact_grad_stats_update.restype = i32
+    lib.gact_footprint.argtypes = [vp, i32, i64, i32, vp, vp, sz, vp]
+    lib.gact_footprint.restype = i32
     lib.gact_variance_alert.argtypes = [vp, vp, i32, ctypes.c_double, ctypes.c_double, vp]
     lib.gact_variance_alert.restype = i32
     return lib
@@ -320,6 +322,20 @@ def gact_grad_stats_update(g: Sequence[torch.Tensor], mean: Sequence[torch.Tenso
                                     workspace.numel(), _stream(stream))
     if rc != GACT_OK:
         raise GactError(rc, "gact_grad_stats_update")
+    return out
+
+
+def gact_footprint(x: torch.Tensor, n_samples: int = 8, out: Optional[torch.Tensor] = None,
+                   workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """-> device float64[1 + n_samples]: sum of x, then n_samples evenly spaced elements."""
+    x = _flat(x)
+    workspace = _reduce_workspace([x], workspace)
+    if out is None:
+        out = torch.empty(1 + n_samples, dtype=torch.float64, device=x.device)
+    rc = lib.gact_footprint(x.data_ptr(), dtype_code(x.dtype), x.numel(), n_samples, out.data_ptr(),
+                            workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if rc != GACT_OK:
+        raise GactError(rc, "gact_footprint")
     return out
 
 

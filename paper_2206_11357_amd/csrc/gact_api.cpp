@@ -319,6 +319,24 @@ int gact_grad_stats_update(const gact_grad_stat* h_stats, int K, int64_t t, doub
                ? GACT_OK : GACT_E_HIP;
 }
 
+int gact_footprint(const void* d_x, gact_dtype dtype, int64_t n, int n_samples, double* d_out,
+                   void* d_workspace, size_t workspace_bytes, void* stream) {
+    if (n < 0 || n_samples < 0 || n_samples > 32768 || !dtype_ok((int)dtype) || !d_out ||
+        !aligned(d_out, 8))
+        return GACT_E_ARG;
+    if (n == 0) return gact_launch_zero(d_out, 1 + n_samples, stream) == 0 ? GACT_OK : GACT_E_HIP;
+    if (!d_x || !aligned(d_x, 16)) return GACT_E_ARG;
+    const int64_t chunk = gact::reduce_chunk_elems((int)dtype);
+    const int64_t blocks = (n + chunk - 1) / chunk;
+    if (blocks > 0x7FFFFFFFll) return GACT_E_ARG;
+    if (!d_workspace || !aligned(d_workspace, 16) ||
+        workspace_bytes < (size_t)blocks * sizeof(double))
+        return GACT_E_ARG;
+    const gact::ReduceArgs r{d_x, nullptr, n, (int32_t)dtype, 0};
+    return gact_launch_footprint(&r, (unsigned)blocks, (double*)d_workspace, n_samples, d_out,
+                                 stream) == 0 ? GACT_OK : GACT_E_HIP;
+}
+
 int gact_variance_alert(const float* h_sensitivity, const int32_t* h_bits, int L, double grad_var,
                         double threshold, double* h_ratio) {
     if (L < 0 || (L > 0 && (!h_sensitivity || !h_bits)) || !(grad_var > 0.0)) return GACT_E_ARG;

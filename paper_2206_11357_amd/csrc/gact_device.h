@@ -77,6 +77,8 @@ extern "C" int gact_launch_single(int compress, const gact::TensorArgs* t,
 extern "C" int gact_launch_diff_sq(const gact::ReduceArgs* d_table, const uint32_t* d_first, int K,
                                    unsigned blocks, double* d_partial, double scale, double* d_out,
                                    void* stream);
+extern "C" int gact_launch_footprint(const gact::ReduceArgs* r, unsigned blocks, double* d_partial,
+                                     int n_samples, double* d_out, void* stream);
 extern "C" int gact_launch_zero(double* d_out, int nout, void* stream);
 extern "C" int gact_launch_grad_stats(const gact::ReduceArgs* d_table, const uint32_t* d_first, int K,
                                       float rt, unsigned blocks, double* d_partial, double* d_out,

@@ -125,6 +125,51 @@ __global__ __launch_bounds__(kRedThreads) void diff_sq_kernel(const ReduceArgs* 
     if (threadIdx.x == 0) partial[b] = s;
 }
 
+// ---------------------------------------------------------------- footprint
+template <int DT, bool FULL>
+__device__ __forceinline__ double sum_chunk(const ReduceArgs& r, int64_t chunk) {
+    constexpr int P = DT == GACT_DT_F32 ? 4 : 8;
+    const int64_t e0 = chunk * (int64_t)(kRedThreads * 4 * P) + (int64_t)threadIdx.x * P;
+    u4r a[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+        a[k] = load_piece16<DT, FULL>(r.a, e0 + (int64_t)k * kRedThreads * P, r.n);
+    double acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        float x[8];
+        unpack_piece<DT>(a[k], x);      // elements past n were loaded as 0
+#pragma unroll
+        for (int j = 0; j < P; ++j) acc += (double)x[j];
+    }
+    return acc;
+}
+
+// one buffer; block b takes chunk b
+__global__ __launch_bounds__(kRedThreads) void sum_kernel(ReduceArgs r, double* __restrict__ partial) {
+    __shared__ double lds[4];
+    const int64_t chunk = (int64_t)blockIdx.x;
+    const bool full = (chunk + 1) * reduce_chunk_elems(r.dtype) <= r.n;
+    double acc;
+    if (r.dtype == GACT_DT_F32)
+        acc = full ? sum_chunk<GACT_DT_F32, true>(r, chunk) : sum_chunk<GACT_DT_F32, false>(r, chunk);
+    else
+        acc = full ? sum_chunk<GACT_DT_BF16, true>(r, chunk) : sum_chunk<GACT_DT_BF16, false>(r, chunk);
+    const double s = block_sum(acc, lds);
+    if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
+// out[1 + j] = element floor(j * n / n_samples) as binary64
+__global__ void sample_kernel(ReduceArgs r, int n_samples, double* __restrict__ out) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= n_samples) return;
+    const int64_t i = (int64_t)(((unsigned __int128)(uint64_t)j * (uint64_t)r.n) / (uint64_t)n_samples);
+    float v;
+    if (r.dtype == GACT_DT_F32) v = ((const float*)r.a)[i];
+    else v = __builtin_bit_cast(float, (uint32_t)((const uint16_t*)r.a)[i] << 16);
+    out[1 + j] = (double)v;
+}
+
 // ------------------------------------------------------- gradient statistics
 template <int DT, bool FULL>
 __device__ __forceinline__ void stats_chunk(const ReduceArgs& r, int64_t chunk, float rt,
@@ -257,5 +302,17 @@ extern "C" int gact_launch_grad_stats(const gact::ReduceArgs* d_table, const uin
 extern "C" int gact_launch_zero(double* d_out, int nout, void* stream) {
     hipLaunchKernelGGL(gact::finish_kernel, dim3(nout), dim3(gact::kFinThreads), 0, (hipStream_t)stream,
                        (const double*)d_out, 0u, 0.0, d_out);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+extern "C" int gact_launch_footprint(const gact::ReduceArgs* r, unsigned blocks, double* d_partial,
+                                     int n_samples, double* d_out, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(gact::sum_kernel, dim3(blocks), dim3(gact::kRedThreads), 0, s, *r, d_partial);
+    hipLaunchKernelGGL(gact::finish_kernel, dim3(1), dim3(gact::kFinThreads), 0, s, d_partial, blocks,
+                       1.0, d_out);
+    if (n_samples > 0)
+        hipLaunchKernelGGL(gact::sample_kernel, dim3((n_samples + 255) / 256), dim3(256), 0, s, *r,
+                           n_samples, d_out);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }

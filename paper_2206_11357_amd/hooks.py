@@ -16,8 +16,8 @@ from typing import Callable, Dict, List, Optional, Sequence
 import numpy as np
 import torch
 
-from . import (GACT_BITS_UNCOMPRESSED, alloc_compressed, gact_allocate_bits_levels,
-               gact_compress, gact_decompress, gact_sensitivity)
+from . import (GACT_BITS_UNCOMPRESSED, gact_allocate_bits_levels, gact_compress, gact_decompress,
+               gact_footprint, gact_sensitivity)
 
 
 @dataclass
@@ -40,12 +40,17 @@ class Controller:
     sensitivities c_l of the context tensors of one model."""
 
     def __init__(self, params: Sequence[torch.Tensor] = (), group_size: int = 256, bits: int = 4,
-                 seed: int = 0, min_numel: int = 1024, swap: bool = False):
+                 seed: int = 0, min_numel: int = 1024, swap: bool = False, dedup: bool = False):
         self.group_size = group_size
         self.default_bits = bits
         self.base_seed = seed
         self.min_numel = min_numel
         self.swap = swap
+        # dedup: a tensor saved by several operators is compressed once.  The data pointer
+        # alone cannot identify it (the allocator hands a freed activation's address to the
+        # next one), so candidates are confirmed by their footprint: sum + sampled points
+        # (Sec. 5.2).  Costs one extra read of every saved tensor.
+        self.dedup = dedup
         self.param_ptrs = {p.data_ptr() for p in params}
         self.bits: Dict[int, int] = {}            # index l -> b_l
         self.seed_override: Dict[int, int] = {}   # index l -> r_l (Alg. 1 reseeds one tensor)
@@ -53,12 +58,14 @@ class Controller:
         self.sensitivity: Optional[np.ndarray] = None
         self._index = 0
         self._live: Dict[int, _Packed] = {}
+        self._by_storage: Dict[tuple, tuple] = {}   # (ptr, numel, dtype) -> (handle, footprint)
         self._side = torch.cuda.Stream() if swap else None     # default priority
 
     # ------------------------------------------------------------- iteration
     def begin_iteration(self) -> None:
         self._index = 0
         self._live.clear()
+        self._by_storage.clear()
         self.numel = []
 
     def seed_of(self, index: int) -> int:
@@ -75,6 +82,12 @@ class Controller:
     def pack(self, x: torch.Tensor):
         if not self._eligible(x):
             return x
+        key = (x.data_ptr(), x.numel(), x.dtype)
+        fp = gact_footprint(x.detach(), 8) if self.dedup else None
+        if self.dedup and key in self._by_storage:
+            h, old_fp = self._by_storage[key]
+            if torch.equal(fp, old_fp):
+                return h                             # saved before in this iteration: share it
         index = self._index
         self._index += 1
         self.numel.append(x.numel())
@@ -86,6 +99,8 @@ class Controller:
         if self.swap:
             self._swap_out(h)
         self._live[index] = h
+        if self.dedup:
+            self._by_storage[key] = (h, fp)
         return h
 
     def unpack(self, h):

@@ -125,3 +125,23 @@ def test_variance_alert_end_to_end(gact):
     assert ratio == pytest.approx(oracle.variance_ratio(c, [2, 4], var), rel=1e-12)
     alert, _ = gact.gact_variance_alert(c, [8, 8], var, 1.5)
     assert not alert
+
+
+@pytest.mark.parametrize("dtype", ("f32", "bf16"))
+def test_footprint_matches_the_oracle(gact, dtype):
+    for n in (1, 3, 7, 4095, 4097, 100001, 1 << 21):
+        x = syn.draw_numpy(syn.NORMAL, n, n % 89)
+        if dtype == "bf16":
+            x = syn.f32_to_bf16_bits(x)
+        for ns in (0, 1, 8, 33):
+            want = oracle.footprint(x, ns)
+            got = gact.gact_footprint(dev(x), ns).cpu().numpy()
+            assert got.shape == want.shape
+            # sum of terms of both signs: absolute bar from the sum of magnitudes
+            mag = float(np.sum(np.abs(syn.bf16_bits_to_f32(x) if dtype == "bf16" else x).astype(np.float64)))
+            assert abs(got[0] - want[0]) <= REL * mag
+            assert np.array_equal(got[1:], want[1:])
+    e = torch.empty(0, device="cuda")
+    assert gact.gact_footprint(e, 4).cpu().numpy().tolist() == [0.0] * 5
+    k = torch.arange(1, 1001, dtype=torch.float32, device="cuda")
+    assert gact.gact_footprint(k, 4).cpu().numpy().tolist() == [500500.0, 1.0, 251.0, 501.0, 751.0]

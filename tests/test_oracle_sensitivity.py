@@ -126,3 +126,25 @@ def test_algorithm_1_on_a_linear_gradient_recovers_the_compression_variance():
     bound = float(np.sum(w.astype(np.float64) ** 2 * 0.25 * step ** 2))
     assert est == pytest.approx(want, rel=0.08)
     assert est <= bound
+
+
+def test_footprint_closed_forms():
+    """Sec. 5.2: duplicates are recognised by sampled points and the sum."""
+    n = 1000
+    k = np.arange(1, n + 1, dtype=np.float32)
+    f = oracle.footprint(k, 4)
+    assert f[0] == n * (n + 1) / 2
+    assert f[1:].tolist() == [1.0, 251.0, 501.0, 751.0]          # elements 0, 250, 500, 750
+    assert oracle.footprint(k, 0).tolist() == [n * (n + 1) / 2]
+    assert oracle.footprint(np.zeros(0, np.float32), 3).tolist() == [0.0, 0.0, 0.0, 0.0]
+    f1 = oracle.footprint(k[:7], 3)
+    assert f1.tolist() == [28.0, 1.0, 3.0, 5.0]                   # floor(j*7/3) = 0, 2, 4
+    kb = syn.f32_to_bf16_bits(np.arange(0, 256, dtype=np.float32))
+    assert oracle.footprint(kb, 2).tolist() == [255 * 256 / 2, 0.0, 128.0]
+    # cancelling terms: exact in the compensated sum
+    x = np.array([1e8, 1.0, -1e8, 1.0] * 1000, np.float32)
+    assert oracle.footprint(x, 0)[0] == 2000.0
+    # a changed element changes the footprint's sum
+    a = syn.draw_numpy(syn.NORMAL, 5000, 3)
+    b = a.copy(); b[1234] += 1e-3
+    assert oracle.footprint(a, 8)[0] != oracle.footprint(b, 8)[0]
