@@ -61,9 +61,7 @@ int make_args(bool compress, const void* x, void* packed, float* gmin, float* gs
     out->seed_lo = (uint32_t)seed;
     out->seed_hi = (uint32_t)(seed >> 32);
     out->tiles = (uint32_t)tiles;
-    out->bits = (uint8_t)bits;
-    out->dtype = (uint8_t)dtype;
-    out->pad[0] = out->pad[1] = 0;
+    out->bits_dtype = (uint32_t)bits | ((uint32_t)dtype << 8);
     return GACT_OK;
 }
 
@@ -71,7 +69,7 @@ int make_args(bool compress, const void* x, void* packed, float* gmin, float* gs
 // a fixed span of elements per block
 int64_t blocks_for(bool compress, const gact::TensorArgs& t) {
     if (compress) return ((int64_t)t.tiles + kWavesPerBlock - 1) / kWavesPerBlock;
-    const int64_t span = gact::dec_block_elems(t.dtype, t.bits);
+    const int64_t span = gact::dec_block_elems(t.dtype(), t.bits());
     return (t.n + span - 1) / span;
 }
 

@@ -5,6 +5,11 @@
 
 #include <stdint.h>
 
+#ifndef __HIPCC__
+#define __host__
+#define __device__
+#endif
+
 #define GACT_DT_F32 0
 #define GACT_DT_BF16 1
 
@@ -19,9 +24,12 @@ struct TensorArgs {
     int64_t     n;         // elements
     uint32_t    seed_lo, seed_hi;
     uint32_t    tiles;     // compress: wavefront tiles covering the tensor
-    uint8_t     bits;
-    uint8_t     dtype;
-    uint8_t     pad[2];
+    // Whole dwords only: a sub-dword field would be fetched with a vector load,
+    // which queues behind the kernel's own HBM traffic at the start of every block,
+    // whereas dword fields of a uniform record come through the scalar cache.
+    uint32_t    bits_dtype;   // bits | dtype << 8
+    __host__ __device__ int bits() const { return (int)(bits_dtype & 0xFFu); }
+    __host__ __device__ int dtype() const { return (int)(bits_dtype >> 8); }
 };
 
 // How a group size maps onto a wavefront: a lane owns 32 consecutive

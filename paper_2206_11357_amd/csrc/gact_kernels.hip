@@ -49,7 +49,7 @@ constexpr int kBlockThreads = kLanes * kWavesPerBlk;
 
 // 32-bit words of the packed buffer: ceil(n*bits/8) bytes rounded up to 16
 __device__ __forceinline__ int64_t packed_words(const TensorArgs& t) {
-    return (int64_t)((((uint64_t)t.n * (uint64_t)t.bits + 127u) >> 7) << 2);
+    return (int64_t)((((uint64_t)t.n * (uint64_t)t.bits() + 127u) >> 7) << 2);
 }
 
 // ---------------------------------------------------------------- lane moves
@@ -73,13 +73,34 @@ __device__ __forceinline__ float lane_read(float v, int src_lane) {
 __device__ __forceinline__ float fmin2(float a, float b) { return __builtin_fminf(a, b); }
 __device__ __forceinline__ float fmax2(float a, float b) { return __builtin_fmaxf(a, b); }
 
+// v = min / max(v, v of the DPP-selected lane) in one instruction.  Written as
+// assembly because the compiler otherwise moves the DPP operand into its own
+// register and re-canonicalises both inputs (4 instructions per step).
+#define GACT_DPP_MINMAX(NAME, OP, CTRL)                                                  \
+    __device__ __forceinline__ float NAME(float v) {                                     \
+        float r;                                                                          \
+        asm(OP " %0, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));  \
+        return r;                                                                         \
+    }
+GACT_DPP_MINMAX(min_xor1, "v_min_f32_dpp", "quad_perm:[1,0,3,2]")
+GACT_DPP_MINMAX(max_xor1, "v_max_f32_dpp", "quad_perm:[1,0,3,2]")
+GACT_DPP_MINMAX(min_xor2, "v_min_f32_dpp", "quad_perm:[2,3,0,1]")
+GACT_DPP_MINMAX(max_xor2, "v_max_f32_dpp", "quad_perm:[2,3,0,1]")
+GACT_DPP_MINMAX(min_half_mirror, "v_min_f32_dpp", "row_half_mirror")
+GACT_DPP_MINMAX(max_half_mirror, "v_max_f32_dpp", "row_half_mirror")
+GACT_DPP_MINMAX(min_mirror, "v_min_f32_dpp", "row_mirror")
+GACT_DPP_MINMAX(max_mirror, "v_max_f32_dpp", "row_mirror")
+#undef GACT_DPP_MINMAX
+
 // All lanes of a group (lpg neighbouring lanes, lpg a power of two <= 32,
-// groups aligned to lpg) end up with the group's min and max.
+// groups aligned to lpg) end up with the group's min and max.  After the two
+// quad steps all lanes of a quad agree, so the 8- and 16-lane mirrors pair
+// each lane with one from the other half.
 __device__ __forceinline__ void group_minmax_pow2(float& mn, float& mx, int lpg) {
-    if (lpg > 1)  { mn = fmin2(mn, dpp<0xB1>(mn));  mx = fmax2(mx, dpp<0xB1>(mx)); }   // lane^1
-    if (lpg > 2)  { mn = fmin2(mn, dpp<0x4E>(mn));  mx = fmax2(mx, dpp<0x4E>(mx)); }   // lane^2
-    if (lpg > 4)  { mn = fmin2(mn, dpp<0x141>(mn)); mx = fmax2(mx, dpp<0x141>(mx)); }  // 7-lane mirror
-    if (lpg > 8)  { mn = fmin2(mn, dpp<0x140>(mn)); mx = fmax2(mx, dpp<0x140>(mx)); }  // 15-lane mirror
+    if (lpg > 1)  { mn = min_xor1(mn);        mx = max_xor1(mx); }
+    if (lpg > 2)  { mn = min_xor2(mn);        mx = max_xor2(mx); }
+    if (lpg > 4)  { mn = min_half_mirror(mn); mx = max_half_mirror(mx); }
+    if (lpg > 8)  { mn = min_mirror(mn);      mx = max_mirror(mx); }
     if (lpg > 16) { mn = fmin2(mn, swizzle_xor16(mn)); mx = fmax2(mx, swizzle_xor16(mx)); }
 }
 
@@ -485,7 +506,7 @@ __device__ __forceinline__ void decompress_units(const TensorArgs& t, const Geom
 // ------------------------------------------------------------------ kernels
 // uniform dispatch over (dtype, bits)
 #define GACT_DISPATCH(t, CALL)                                                       \
-    switch ((t).dtype * 16 + (t).bits) {                                             \
+    switch ((t).dtype() * 16 + (t).bits()) {                                             \
         case GACT_DT_F32 * 16 + 1:  { CALL(GACT_DT_F32, 1) } break;                  \
         case GACT_DT_F32 * 16 + 2:  { CALL(GACT_DT_F32, 2) } break;                  \
         case GACT_DT_F32 * 16 + 4:  { CALL(GACT_DT_F32, 4) } break;                  \
@@ -519,7 +540,7 @@ __device__ __forceinline__ void decompress_block(const TensorArgs& t, const Geom
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     // full: every element of the block's span exists
-    const bool full = (block_in_tensor + 1) * (int64_t)dec_block_elems(t.dtype, t.bits) <= t.n;
+    const bool full = (block_in_tensor + 1) * (int64_t)dec_block_elems(t.dtype(), t.bits()) <= t.n;
 #define GACT_D_FULL(DT, BITS) \
     decompress_units<DT, BITS, false, dec_units_per_wave(DT, BITS)>(t, geo, block_in_tensor, wave, lane);
 #define GACT_D_EDGE(DT, BITS) \
