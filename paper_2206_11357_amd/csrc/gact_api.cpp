@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstring>
 #include <queue>
+#include <algorithm>
 #include <vector>
 
 #include "gact.h"
@@ -31,6 +32,7 @@ gact::Geometry make_geometry(int group_size) {
     geo.groups_per_tile = geo.lanes_used / geo.lpg;
     geo.group_size = group_size;
     geo.group_shift = geo.lpg_shift + 5;
+    geo.lds_wave_dwords = 0;      // set per launch from the dtypes in it
     return geo;
 }
 
@@ -89,7 +91,7 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
     if (!group_ok(group_size)) return GACT_E_GROUP;
     if (L == 0) return GACT_OK;
     if (!descs) return GACT_E_ARG;
-    const gact::Geometry geo = make_geometry(group_size);
+    gact::Geometry geo = make_geometry(group_size);
 
     // one contiguous staging image: table of the non-empty tensors, then the
     // first block of each, then the total
@@ -111,6 +113,7 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
         if (d.n == 0) continue;
         first.push_back((uint32_t)blocks);
         table.push_back(t);
+        geo.lds_wave_dwords = std::max(geo.lds_wave_dwords, gact::lds_dwords_per_wave(d.dtype));
         blocks += (uint64_t)blocks_for(compress, t);
         if (blocks > 0x7FFFFFFFull) return GACT_E_ARG;
     }
@@ -221,7 +224,8 @@ int gact_compress(const void* d_x, gact_dtype dtype, int64_t n, int group_size, 
                   uint64_t seed, void* d_packed, float* d_gmin, float* d_gscale, void* stream) {
     if (!bits_ok(bits)) return GACT_E_BITS;
     if (!group_ok(group_size)) return GACT_E_GROUP;
-    const gact::Geometry geo = make_geometry(group_size);
+    gact::Geometry geo = make_geometry(group_size);
+    geo.lds_wave_dwords = gact::lds_dwords_per_wave((int)dtype);
     gact::TensorArgs t;
     const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, bits,
                              (int)dtype, geo, &t);

@@ -43,7 +43,12 @@ struct Geometry {
     int32_t groups_per_tile;
     int32_t group_size;
     int32_t group_shift;   // log2(group_size) when pow2
+    int32_t lds_wave_dwords;   // compress: LDS dwords per wavefront (lds_dwords_per_wave of the widest dtype launched)
 };
+
+// LDS one compressing wavefront stages its tile in: 64 rows of 32 elements in
+// the input's own format.
+constexpr int lds_dwords_per_wave(int dtype) { return dtype == GACT_DT_F32 ? 64 * 32 : 64 * 16; }
 
 // A launch table small enough to travel in the kernel arguments (4 KB limit).
 constexpr int kInlineTensors = 64;

@@ -13,9 +13,12 @@
 //     once per 32 elements.
 //   * HBM is read with fully coalesced 16-byte loads (lane i of load k reads
 //     bytes [k*1024 + 16 i, +16)).  The switch from that layout to "32
-//     consecutive elements per lane" goes through a private, padded LDS region
-//     per wavefront (row stride 36 dwords: conflict-free 128-bit LDS reads and
-//     writes).
+//     consecutive elements per lane" goes through a private LDS region per
+//     wavefront, in the input's own format (8 KB for fp32, 4 KB for bf16; the
+//     16-byte pieces of a row are XOR-swizzled so that 128-bit LDS reads and
+//     writes are conflict-free without padding).  The LDS a wavefront holds
+//     bounds how many are resident, so the launch sizes it by the widest dtype
+//     present.
 //   * With 32 elements per lane a lane owns 32*bits packed bits = `bits`
 //     dwords, and neighbouring lanes own neighbouring dwords: the packed
 //     stream is written coalesced without further staging.
@@ -42,8 +45,6 @@ typedef uint32_t u2 __attribute__((ext_vector_type(2)));
 
 constexpr int kLanes        = 64;
 constexpr int kPerLane      = 32;                 // consecutive elements one lane owns
-constexpr int kRowDwords    = kPerLane + 4;       // padded LDS row of one lane
-constexpr int kWaveLdsDw    = kLanes * kRowDwords;
 constexpr int kWavesPerBlk  = 4;
 constexpr int kBlockThreads = kLanes * kWavesPerBlk;
 
@@ -208,37 +209,58 @@ __device__ __forceinline__ void load_tile(const void* __restrict__ x, int64_t e0
     }
 }
 
-// Raw tile -> LDS rows (row r = elements 32 r .. 32 r + 31), as fp32; bf16 is
-// widened here, exactly.
+// Raw tile -> LDS rows (row r = elements 32 r .. 32 r + 31) in the input's own
+// format: 8 (fp32) or 4 (bf16) pieces of 16 bytes per row.  Staging bf16
+// unwidened halves the LDS a wavefront holds, which is what bounds the number
+// of resident wavefronts.  Rows are not padded; piece p of row r sits at slot
+// p ^ s(r), with s(r) = (r >> 1) & 7 for fp32 and (r >> 2) & 3 for bf16.  A
+// 128-bit LDS access is served 16 lanes at a time over 64 banks:
+//   * writes: 16 neighbouring lanes hold 16 consecutive pieces, i.e. all slots
+//     of 2 (4) neighbouring rows that share s(r) -> 16 distinct bank quads;
+//   * reads: 16 neighbouring lanes read the same piece index of 16 consecutive
+//     rows; the row's own offset covers 2 (4) bank quads and s(r) runs through
+//     the 8 (4) values that complete them.
 template <int DT>
-__device__ __forceinline__ void stage_tile(const RawTile<DT>& raw, float* __restrict__ lds,
+__device__ __forceinline__ void stage_tile(const RawTile<DT>& raw, uint32_t* __restrict__ lds,
                                            int lane) {
     if (DT == GACT_DT_F32) {
+        // load k, lane L: row 8 k + L / 8, piece L % 8, s = (4 k + L / 16) & 7
+        uint32_t* base = lds + (lane >> 3) * 32;
+        const int slot0 = ((lane & 7) ^ (lane >> 4)) * 4;          // even k
+        const int slot1 = slot0 ^ 16;                              // odd k
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int e = k * 256 + lane * 4;
-            *(u4*)(lds + (e >> 5) * kRowDwords + (e & 31)) = raw.r[k];
-        }
+        for (int k = 0; k < 8; ++k)
+            *(u4*)(base + k * 256 + ((k & 1) ? slot1 : slot0)) = raw.r[k];
     } else {
+        // load k, lane L: row 16 k + L / 4, piece L % 4, s = (L / 16) & 3
+        uint32_t* base = lds + (lane >> 2) * 16 + (((lane & 3) ^ (lane >> 4)) * 4);
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int e = k * 512 + lane * 8;
-            const u4 w = raw.r[k];
-            float* row = lds + (e >> 5) * kRowDwords + (e & 31);
-            const u4 lo = {w.x << 16, w.x & 0xFFFF0000u, w.y << 16, w.y & 0xFFFF0000u};
-            const u4 hi = {w.z << 16, w.z & 0xFFFF0000u, w.w << 16, w.w & 0xFFFF0000u};
-            *(u4*)(row) = lo;
-            *(u4*)(row + 4) = hi;
-        }
+        for (int k = 0; k < 4; ++k) *(u4*)(base + k * 256) = raw.r[k];
     }
 }
 
-__device__ __forceinline__ void read_row(const float* __restrict__ lds, int row, float v[kPerLane]) {
-    const float* p = lds + row * kRowDwords;
+// The lane's own row as fp32; bf16 is widened here, exactly.
+template <int DT>
+__device__ __forceinline__ void read_row(const uint32_t* __restrict__ lds, int row, float v[kPerLane]) {
+    if (DT == GACT_DT_F32) {
+        const uint32_t first = (uint32_t)row * 32u + (((uint32_t)row >> 1) & 7u) * 4u;   // piece 0
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        const f4 q = *(const f4*)(p + 4 * k);
-        v[4 * k + 0] = q.x; v[4 * k + 1] = q.y; v[4 * k + 2] = q.z; v[4 * k + 3] = q.w;
+        for (int k = 0; k < 8; ++k) {
+            const f4 q = *(const f4*)(lds + (first ^ (uint32_t)(4 * k)));
+            v[4 * k + 0] = q.x; v[4 * k + 1] = q.y; v[4 * k + 2] = q.z; v[4 * k + 3] = q.w;
+        }
+    } else {
+        const uint32_t first = (uint32_t)row * 16u + (((uint32_t)row >> 2) & 3u) * 4u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const u4 w = *(const u4*)(lds + (first ^ (uint32_t)(4 * k)));
+            const uint32_t h[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                v[8 * k + 2 * j + 0] = __builtin_bit_cast(float, h[j] << 16);
+                v[8 * k + 2 * j + 1] = __builtin_bit_cast(float, h[j] & 0xFFFF0000u);
+            }
+        }
     }
 }
 
@@ -264,7 +286,7 @@ __device__ __forceinline__ void wave_lds_sync() {
 //   geo.lanes_used lanes that hold data in a full tile (64 for power-of-two G)
 template <int DT, int BITS, bool EDGE>
 __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometry& geo,
-                                              int64_t tile, float* __restrict__ lds, int lane) {
+                                              int64_t tile, uint32_t* __restrict__ lds, int lane) {
     constexpr uint32_t B = (1u << BITS) - 1u;
     const int tile_elems = geo.lanes_used * kPerLane;
     const int64_t e0 = tile * (int64_t)tile_elems;
@@ -281,7 +303,7 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
     float v[kPerLane];
     stage_tile<DT>(raw, lds, lane);
     wave_lds_sync();
-    read_row(lds, lane, v);
+    read_row<DT>(lds, lane, v);
 
     // group statistics
     const int my0 = lane * kPerLane;                 // first element of this lane in the tile
@@ -520,10 +542,11 @@ __device__ __forceinline__ void decompress_units(const TensorArgs& t, const Geom
 
 __device__ __forceinline__ void compress_block(const TensorArgs& t, const Geometry& geo,
                                                int64_t block_in_tensor) {
-    __shared__ __attribute__((aligned(16))) float lds_all[kWavesPerBlk * kWaveLdsDw];
+    // sized by the launcher: geo.lds_wave_dwords per wavefront
+    extern __shared__ __attribute__((aligned(16))) uint32_t lds_all[];
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
-    float* lds = lds_all + wave * kWaveLdsDw;
+    uint32_t* lds = lds_all + wave * geo.lds_wave_dwords;
     const int64_t tile = block_in_tensor * kWavesPerBlk + wave;
     if (tile >= (int64_t)t.tiles) return;
     // a tile is "full" when all its elements exist and G is a power of two
@@ -599,21 +622,23 @@ __global__ __launch_bounds__(kBlockThreads) void multi_inline_kernel(InlineTable
 extern "C" int gact_launch_single(int compress, const gact::TensorArgs* t, const gact::Geometry* geo,
                                   unsigned blocks, void* stream) {
     hipStream_t s = (hipStream_t)stream;
+    const unsigned lds = compress ? 4u * gact::kWavesPerBlk * (unsigned)geo->lds_wave_dwords : 0u;
     if (compress)
-        hipLaunchKernelGGL(gact::single_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), 0, s, *t, *geo);
+        hipLaunchKernelGGL(gact::single_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), lds, s, *t, *geo);
     else
-        hipLaunchKernelGGL(gact::single_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), 0, s, *t, *geo);
+        hipLaunchKernelGGL(gact::single_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), lds, s, *t, *geo);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 extern "C" int gact_launch_multi_inline(int compress, const gact::InlineTable* tab,
                                         const gact::Geometry* geo, unsigned blocks, void* stream) {
     hipStream_t s = (hipStream_t)stream;
+    const unsigned lds = compress ? 4u * gact::kWavesPerBlk * (unsigned)geo->lds_wave_dwords : 0u;
     if (compress)
-        hipLaunchKernelGGL(gact::multi_inline_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), 0, s,
+        hipLaunchKernelGGL(gact::multi_inline_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), lds, s,
                            *tab, *geo);
     else
-        hipLaunchKernelGGL(gact::multi_inline_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), 0, s,
+        hipLaunchKernelGGL(gact::multi_inline_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), lds, s,
                            *tab, *geo);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
@@ -622,11 +647,12 @@ extern "C" int gact_launch_multi(int compress, const gact::TensorArgs* d_table,
                                  const uint32_t* d_first_block, int L, const gact::Geometry* geo,
                                  unsigned blocks, void* stream) {
     hipStream_t s = (hipStream_t)stream;
+    const unsigned lds = compress ? 4u * gact::kWavesPerBlk * (unsigned)geo->lds_wave_dwords : 0u;
     if (compress)
-        hipLaunchKernelGGL(gact::multi_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), 0, s,
+        hipLaunchKernelGGL(gact::multi_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), lds, s,
                            d_table, d_first_block, L, *geo);
     else
-        hipLaunchKernelGGL(gact::multi_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), 0, s,
+        hipLaunchKernelGGL(gact::multi_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), lds, s,
                            d_table, d_first_block, L, *geo);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
