@@ -11,7 +11,14 @@ directions: (bytes read by compress + bytes written by decompress) / time.
 (sizeof(T) + bits/8 + 8/G per element) against the 8 TB/s HBM3E peak, with its
 launch duration measured by events on the launch stream inside the timed
 steps.  `cpu_baseline` is the CPU oracle timed on a bounded sample of the same
-tensors on the host cores.
+tensors on the host cores (all threads, and one thread on a smaller sample).
+Also on the line: the same set through one single-tensor call per tensor
+(`per_tensor_calls`), a plain device copy's GB/s on the same box
+(`copy_ceiling`), and the HBM peak the device properties give.
+
+`--workload single_1m` times the single-tensor calls on 1,048,576 fp32 elements
+(launch bound, 4 MiB) over a ring of 128 distinct buffers so that no call finds
+its input in a cache.
 """
 from __future__ import annotations
 
@@ -46,7 +53,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="resnet50_b64",
-                    choices=sorted(WORKLOADS) + ["grad_sensitivity"])
+                    choices=sorted(WORKLOADS) + ["grad_sensitivity", "single_1m"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=800_000_000)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -82,6 +89,8 @@ def main() -> int:
 
     if args.workload == "grad_sensitivity":
         return bench_grad_sensitivity(args, gact, torch, np, dev)
+    if args.workload == "single_1m":
+        return bench_single_1m(args, gact, torch, np, dev)
 
     builder, G, avg_bits, sens_seed, desc = WORKLOADS[args.workload]
     specs = getattr(syn, builder)()
@@ -158,6 +167,24 @@ def main() -> int:
     except OSError:
         traffic = None
 
+    # the same set, one single-tensor call per tensor and direction
+    def per_tensor(record: bool):
+        e0, e1, e2 = ev(), ev(), ev()
+        if record: e0.record()
+        for l in range(L):
+            gact.gact_compress(xs[l], G, int(bits[l]), seeds[l], packed[l], gmin[l], gscale[l])
+        if record: e1.record()
+        for l in range(L):
+            gact.gact_decompress(packed[l], gmin[l], gscale[l], int(numel[l]), G, int(bits[l]), dts[l], ys[l])
+        if record: e2.record()
+        return e0, e1, e2
+    per_tensor(False)
+    torch.cuda.synchronize()
+    pt = [per_tensor(True) for _ in range(max(args.steps // 4, 3))]
+    torch.cuda.synchronize()
+    pt_c = float(np.median([a.elapsed_time(b) for a, b, _ in pt]))
+    pt_d = float(np.median([b.elapsed_time(c) for _, b, c in pt]))
+
     out = {
         "metric": "compress+decompress GB/s (input bytes) and % of HBM peak, 1xMI355X",
         "value": round(value, 2),
@@ -169,7 +196,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32",
+        "dtype": specs[0].dtype,
         "data": "synthetic",
         "config": {
             "workload": args.workload, "description": desc, "tensors": L, "elements": n_total,
@@ -189,6 +216,10 @@ def main() -> int:
                      "kernel": "gact::multi_inline_kernel<true>" if L <= 64 else "gact::multi_kernel<true>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic},
+        "per_tensor_calls": {"calls_per_direction": L, "compress_ms": round(pt_c, 4), "decompress_ms": round(pt_d, 4),
+                             "fused_pct_hbm_peak": round(100 * 2 * alg_bytes / (pt_c + pt_d) / 1e6 / HBM_PEAK_GBPS, 2)},
+        "copy_ceiling": copy_ceiling(torch, np, dev),
+        "hbm_peak": hbm_peak_info(torch),
     }
 
     if not args.no_cpu_baseline:
@@ -213,13 +244,108 @@ def main() -> int:
             oracle.decompress(p, mn, sc, h.size, G, int(bits[l]),
                               oracle.BF16 if h.dtype == np.uint16 else oracle.F32)
         t2 = time.perf_counter()
+        all_threads = oracle.threads()
+        # one thread, on the first 32 Mi elements of the first tensor
+        h1 = host[0][: 1 << 25]
+        oracle.set_threads(1)
+        t3 = time.perf_counter()
+        p1, mn1, sc1 = oracle.compress(h1, G, int(bits[take[0]]), seeds[take[0]])
+        oracle.decompress(p1, mn1, sc1, h1.size, G, int(bits[take[0]]),
+                          oracle.BF16 if h1.dtype == np.uint16 else oracle.F32)
+        t4 = time.perf_counter()
+        oracle.set_threads(all_threads)
         out["cpu_baseline"] = {
             "value": round(2.0 * sample_bytes / (t2 - t0) / 1e9, 3), "unit": "GB/s",
-            "cores": oracle.threads(), "kind": "oracle",
+            "cores": all_threads, "kind": "oracle",
             "sample": "first %d tensors of the set (%d elements, %.2f GB), compress %.2f s + decompress %.2f s"
                       % (len(take), acc, sample_bytes / 1e9, t1 - t0, t2 - t1),
+            "value_1_thread": round(2.0 * h1.nbytes / (t4 - t3) / 1e9, 3),
+            "sample_1_thread": "first %d elements of the first tensor, %.2f s" % (h1.size, t4 - t3),
         }
     print(json.dumps(out))
+    return 0
+
+
+def copy_ceiling(torch, np, dev) -> dict:
+    """A plain device-to-device copy of 1 GiB on this machine: GB/s in read + written bytes."""
+    src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    ms = []
+    for _ in range(10):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); dst.copy_(src); b.record(); b.synchronize()
+        ms.append(a.elapsed_time(b))
+    m = float(np.median(ms))
+    return {"kernel": "torch copy_ of 1 GiB", "GBps_read_plus_write": round(2 * src.numel() * 4 / m / 1e6, 1),
+            "pct_hbm_peak": round(100 * 2 * src.numel() * 4 / m / 1e6 / HBM_PEAK_GBPS, 2)}
+
+
+def hbm_peak_info(torch) -> dict:
+    """The denominator used, and what the device properties give (clock x bus width x 2)."""
+    info = {"used_GBps": HBM_PEAK_GBPS, "source": "published MI355X HBM3E bandwidth"}
+    try:
+        p = torch.cuda.get_device_properties(0)
+        khz, width = getattr(p, "memory_clock_rate", None), getattr(p, "memory_bus_width", None)
+        if khz and width:
+            info["device_props_GBps"] = round(2.0 * khz * 1e3 * width / 8 / 1e9, 1)
+            info["memory_clock_khz"], info["memory_bus_width_bits"] = int(khz), int(width)
+        info["device"] = p.name
+    except Exception as e:                                   # properties missing on this build
+        info["device_props_error"] = str(e)
+    return info
+
+
+def bench_single_1m(args, gact, torch, np, dev) -> int:
+    """Single-tensor calls on 1,048,576 fp32 elements (N(0,1), 1 % outliers x10), G=256, 2 bits,
+    over a ring of 128 distinct buffers (512 MiB of inputs) so that no call is served from a cache."""
+    import synthetic_inputs as syn
+    ring, n, G, b = 128, 1 << 20, 256, 2
+    base = torch.from_numpy(syn.config1()["x"]).to(dev)
+    xs = [base.clone().mul_(1.0 + 0.001 * k) for k in range(ring)]
+    bufs = [gact.alloc_compressed(n, G, b, dev) for _ in range(ring)]
+    ys = [torch.empty_like(x) for x in xs]
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def sweep(record):
+        e0, e1, e2 = ev(), ev(), ev()
+        if record: e0.record()
+        for k in range(ring):
+            gact.gact_compress(xs[k], G, b, 0, *bufs[k])
+        if record: e1.record()
+        for k in range(ring):
+            gact.gact_decompress(*bufs[k], n, G, b, torch.float32, ys[k])
+        if record: e2.record()
+        return e0, e1, e2
+    for _ in range(args.warmup):
+        sweep(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks = [sweep(True) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    c_us = np.array([a.elapsed_time(b) for a, b, _ in marks]) * 1e3 / ring
+    d_us = np.array([b.elapsed_time(c) for _, b, c in marks]) * 1e3 / ring
+    alg = n * 4 + n * b // 8 + (n // G) * 8
+    cm, dm = float(np.median(c_us)), float(np.median(d_us))
+    print(json.dumps({
+        "metric": "compress+decompress GB/s (input bytes) and % of HBM peak, 1xMI355X",
+        "value": round(2 * n * 4 / ((cm + dm) * 1e-6) / 1e9, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / args.steps, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "single_1m", "elements": n, "group_size": G, "bits": b, "ring_buffers": ring,
+                   "description": "one step = 128 compress calls then 128 decompress calls, each on its own 4 MiB tensor; "
+                                  "back-to-back launches on one stream, so the per-call time is the launch-bound issue rate"},
+        "compress": {"us_per_call_median": round(cm, 2), "us_per_call_min": round(float(c_us.min()), 2),
+                     "pct_hbm_peak": round(100 * alg / cm / 1e3 / HBM_PEAK_GBPS, 2)},
+        "decompress": {"us_per_call_median": round(dm, 2), "us_per_call_min": round(float(d_us.min()), 2),
+                       "pct_hbm_peak": round(100 * alg / dm / 1e3 / HBM_PEAK_GBPS, 2)},
+        "roofline": {"bound": "hbm", "kernel": "gact::single_kernel<true>", "achieved": round(alg / cm / 1e3, 1),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(alg / cm / 1e3 / HBM_PEAK_GBPS, 4),
+                     "traffic": None},
+    }))
     return 0
 
 

@@ -51,6 +51,8 @@ def lib() -> ctypes.CDLL:
         L.gact_oracle_philox4x32_10.restype = None
         L.gact_oracle_threads.argtypes = []
         L.gact_oracle_threads.restype = i32
+        L.gact_oracle_set_threads.argtypes = [i32]
+        L.gact_oracle_set_threads.restype = None
         L.gact_oracle_noise.argtypes = [u64, u64]
         L.gact_oracle_noise.restype = ctypes.c_float
         L.gact_oracle_noise_fill.argtypes = [u64, u64, i64, vp]
@@ -106,6 +108,11 @@ def philox4x32_10(ctr, key) -> np.ndarray:
 
 def threads() -> int:
     return int(lib().gact_oracle_threads())
+
+
+def set_threads(n: int) -> None:
+    """Run the oracle's loops on n threads from now on (results do not depend on it)."""
+    lib().gact_oracle_set_threads(int(n))
 
 
 def noise(seed: int, i: int) -> float:

@@ -54,6 +54,16 @@ int gact_oracle_threads(void)
 #endif
 }
 
+/* limit the loops to n threads (n >= 1); used to time the oracle on one core */
+void gact_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 /* ------------------------------------------------------------------ Philox */
 /*
  * Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).  One round:
