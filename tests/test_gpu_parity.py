@@ -300,3 +300,26 @@ def test_uncompressed_level_is_skipped_by_the_multi_calls(gact):
         nb = p_ref.size
         assert np.array_equal(bufs[l][0][:nb].cpu().numpy(), p_ref)
         assert np.array_equal(ys[l].cpu().numpy(), oracle.decompress(p_ref, mn_ref, sc_ref, ns[l], G, int(bits[l])))
+
+
+# ------------------------------------------------------------- frozen digests
+def test_hip_path_reproduces_the_oracle_s_frozen_digests(gact):
+    """The digests in tests/golden/oracle_digests.txt were written from the CPU
+    oracle alone; the HIP path must hash to the same values on the same inputs."""
+    import hashlib
+    here = os.path.dirname(os.path.abspath(__file__))
+    sys.path.insert(0, os.path.join(here, "golden"))
+    import make_golden
+    with open(os.path.join(here, "golden", "oracle_digests.txt")) as f:
+        stored = {ln.split()[0]: dict(kv.split("=") for kv in ln.split()[1:])
+                  for ln in f if not ln.startswith("#")}
+    sha = lambda a: hashlib.sha256(np.ascontiguousarray(a).tobytes()).hexdigest()
+    for name, x, G, b, seed in make_golden.codec_cases():
+        want = stored[name]
+        assert sha(x) == want["input"], name
+        xd = to_device(x)
+        p, mn, sc = gact.gact_compress(xd, G, b, seed)
+        y = gact.gact_decompress(p, mn, sc, x.size, G, b, dtype=xd.dtype)
+        assert sha(to_host(p)) == want["packed"], name
+        assert sha(to_host(mn)) == want["gmin"] and sha(to_host(sc)) == want["gscale"], name
+        assert sha(to_host(y)) == want["dequantised"], name

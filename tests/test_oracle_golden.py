@@ -1,0 +1,32 @@
+"""The oracle still produces the frozen digests in tests/golden/oracle_digests.txt.
+
+The file is written by tests/golden/make_golden.py, which calls only the CPU
+oracle; a mismatch in `input=` means the seeded generators moved, any other
+field that the oracle's arithmetic or noise stream changed."""
+import os
+import sys
+
+import numpy as np
+import pytest
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, os.path.join(HERE, "golden"))
+import make_golden  # noqa: E402
+
+
+def stored():
+    with open(os.path.join(HERE, "golden", "oracle_digests.txt")) as f:
+        return [ln.rstrip("\n") for ln in f]
+
+
+def test_oracle_reproduces_the_frozen_digests():
+    fresh = list(make_golden.lines())
+    old = stored()
+    assert len(fresh) == len(old)
+    for a, b in zip(fresh, old):
+        assert a == b
+
+
+def test_digest_file_covers_every_case_once():
+    names = [ln.split()[0] for ln in stored() if not ln.startswith("#")]
+    assert len(names) == len(set(names)) == 7
