@@ -3,6 +3,9 @@ same seeded inputs.  Packed codes, group minima and steps must be bit-exact;
 dequantised values within 1e-6 relative (fp32) / one bf16 ulp -- in practice
 they are compared for equality first and the tolerance is the stated bar.
 Quantizer: arXiv 2206.11357 App. A.4, per group (Sec. 5)."""
+import os
+import sys
+
 import numpy as np
 import pytest
 import torch
