@@ -33,6 +33,12 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
+# Plain (non-packed, non-matrix) 32-bit vector rate: 256 CUs x 128 lanes x 2.4 GHz, the rate behind the
+# published 157.3 TFLOP/s of fp32 vector FMA.  Multiplies, conversions and three-operand integer
+# instructions issue at half of it.
+VALU_PEAK_LANE_OPS = 256 * 128 * 2.4e9
+# VALU instructions per element of the compress kernel, from SQ_INSTS_VALU x 64 / elements (profiles/)
+COMPRESS_VALU_PER_ELEMENT = {"f32": 16.5, "bf16": 18.3}
 
 WORKLOADS = {
     # name: (set builder, group size, average bits, sensitivity seed, description)
@@ -216,6 +222,11 @@ def main() -> int:
                      "kernel": "gact::multi_inline_kernel<true>" if L <= 64 else "gact::multi_kernel<true>", "achieved": round(achieved, 1),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic},
+        "roofline_alu": {"bound": "alu", "kernel": "compress",
+                         "achieved": round(COMPRESS_VALU_PER_ELEMENT[specs[0].dtype] * n_total / c_avg * 1e3, 0),
+                         "peak": VALU_PEAK_LANE_OPS, "unit": "lane-ops/s",
+                         "frac": round(COMPRESS_VALU_PER_ELEMENT[specs[0].dtype] * n_total / c_avg * 1e3 / VALU_PEAK_LANE_OPS, 4),
+                         "note": "secondary bound; about half of the instruction mix issues at half rate"},
         "per_tensor_calls": {"calls_per_direction": L, "compress_ms": round(pt_c, 4), "decompress_ms": round(pt_d, 4),
                              "fused_pct_hbm_peak": round(100 * 2 * alg_bytes / (pt_c + pt_d) / 1e6 / HBM_PEAK_GBPS, 2)},
         "copy_ceiling": copy_ceiling(torch, np, dev),
