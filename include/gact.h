@@ -73,7 +73,9 @@ enum {
     GACT_E_BITS   = -2,  /* bits not in {1,2,4,8} */
     GACT_E_GROUP  = -3,  /* group_size not a multiple of 32 in [32, 1024] */
     GACT_E_BUDGET = -4,  /* avg_bit_budget < 1 or NaN: no feasible scheme */
-    GACT_E_HIP    = -5   /* the HIP runtime refused the launch or copy */
+    GACT_E_HIP    = -5,  /* the HIP runtime refused the launch or copy */
+    GACT_E_CAPTURE = -6  /* the stream is being captured into a HIP graph and this call
+                            would have to upload a table from host memory */
 };
 
 /* ceil(n / group_size); 0 when n <= 0 or group_size <= 0. */
@@ -123,6 +125,11 @@ int gact_decompress(const void *d_packed, const float *d_gmin,
  *                    arguments and leave it untouched.
  * A table in the workspace is uploaded with a stream-ordered copy from host
  * memory the call owns; h_descs may be reused as soon as the call returns.
+ * HIP graphs: with at most 64 non-empty tensors a call enqueues exactly one
+ * kernel and can be captured (pointers, sizes, bits and seeds are baked into
+ * the node).  A larger table needs an upload from host memory the call owns,
+ * which a graph could not replay: on a capturing stream such a call enqueues
+ * nothing and returns GACT_E_CAPTURE -- capture those sets in slices of 64.
  * A descriptor with bits == GACT_BITS_UNCOMPRESSED is skipped by both calls:
  * the allocator left that tensor at full precision and the caller keeps it.
  * L == 0, or all n == 0, is GACT_OK and launches nothing.
@@ -160,6 +167,9 @@ int gact_decompress_multi(const gact_tensor_desc *h_descs, int L, int group_size
  *   d_workspace  device scratch, >= gact_reduce_workspace_bytes(K, sum of n),
  *                16-byte aligned; in use until the enqueued kernels have run.
  * K == 0 or all n == 0 writes 0.
+ * The buffer table is uploaded from host memory the call owns, so this call
+ * and gact_grad_stats_update return GACT_E_CAPTURE, with nothing enqueued, on
+ * a stream that is being captured into a HIP graph.
  */
 typedef struct {
     const void *g0;

@@ -26,6 +26,7 @@ GACT_E_BITS = -2
 GACT_E_GROUP = -3
 GACT_E_BUDGET = -4
 GACT_E_HIP = -5
+GACT_E_CAPTURE = -6
 
 EXPORTS = (
     "gact_num_groups", "gact_packed_bytes", "gact_error_string", "gact_compress",

@@ -83,6 +83,14 @@ int run_single(bool compress, const gact::TensorArgs& t, const gact::Geometry& g
                ? GACT_OK : GACT_E_HIP;
 }
 
+// A table upload reads host memory that is gone when a captured graph replays.
+// GACT_OK when `stream` is not capturing.
+int refuse_if_capturing(void* stream) {
+    hipStreamCaptureStatus status = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)stream, &status) != hipSuccess) return GACT_E_HIP;
+    return status == hipStreamCaptureStatusNone ? GACT_OK : GACT_E_CAPTURE;
+}
+
 size_t table_bytes(int L) { return ((size_t)L * sizeof(gact::TensorArgs) + 15) / 16 * 16; }
 
 int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_size,
@@ -136,6 +144,7 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
                    ? GACT_OK : GACT_E_HIP;
     }
 
+    if (const int rc = refuse_if_capturing(stream)) return rc;
     const size_t tb = table_bytes(live);
     std::vector<unsigned char> image(tb + first.size() * sizeof(uint32_t));
     std::memcpy(image.data(), table.data(), (size_t)live * sizeof(gact::TensorArgs));
@@ -178,6 +187,7 @@ int stage_reduction(const std::vector<gact::ReduceArgs>& bufs, void* d_workspace
     const size_t tb = reduce_table_bytes(K);
     const size_t need = tb + (size_t)nout * blocks * sizeof(double);
     if (!d_workspace || !aligned(d_workspace, 16) || workspace_bytes < need) return GACT_E_ARG;
+    if (const int rc = refuse_if_capturing(stream)) return rc;
     std::vector<unsigned char> image(tb);
     std::memcpy(image.data(), live.data(), (size_t)K * sizeof(gact::ReduceArgs));
     std::memcpy(image.data() + (size_t)K * sizeof(gact::ReduceArgs), first.data(),
@@ -216,6 +226,7 @@ const char* gact_error_string(int code) {
         case GACT_E_GROUP: return "group_size must be a multiple of 32 in [32, 1024]";
         case GACT_E_BUDGET: return "avg_bit_budget must be >= 1";
         case GACT_E_HIP: return "HIP runtime error";
+        case GACT_E_CAPTURE: return "the stream is capturing a HIP graph and this call needs a table upload from host memory";
         default: return "unknown error";
     }
 }

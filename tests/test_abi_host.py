@@ -80,6 +80,7 @@ def test_argument_errors_are_reported_before_any_launch():
     d[1].bits = 2; d[0].n = 0; d[1].n = 0
     assert lib.gact_decompress_multi(addr, 2, 32, None, 0, None) == gact.GACT_OK       # nothing to do
     assert "bits" in gact.error_string(gact.GACT_E_BITS)
+    assert "captur" in gact.error_string(gact.GACT_E_CAPTURE)
 
 
 @pytest.mark.parametrize("seed", range(60))

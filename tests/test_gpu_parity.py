@@ -326,3 +326,92 @@ def test_hip_path_reproduces_the_oracle_s_frozen_digests(gact):
         assert sha(to_host(p)) == want["packed"], name
         assert sha(to_host(mn)) == want["gmin"] and sha(to_host(sc)) == want["gscale"], name
         assert sha(to_host(y)) == want["dequantised"], name
+
+
+# ------------------------------------------------------------------ HIP graphs
+def test_multi_launches_replay_correctly_from_a_captured_graph(gact):
+    """Up to 64 tensors the launch table travels in the kernel arguments, so a
+    compress + decompress pair is two kernel nodes and nothing else.  The graph
+    is replayed several times on changed inputs, with eager work and
+    synchronisation in between, and every replay is checked against the oracle."""
+    G, L = 256, 6
+    ns = [5000, 8192, 70001, 1, 33000, 2048 * 9]
+    bits = [2, 4, 1, 8, 2, 4]
+    seeds = [11, 12, 13, 14, 15, 16]
+    dts = [torch.float32, torch.bfloat16, torch.float32, torch.float32, torch.bfloat16, torch.float32]
+    xs = [torch.zeros(n, device="cuda", dtype=dt) for n, dt in zip(ns, dts)]
+    bufs = [gact.alloc_compressed(n, G, b, "cuda") for n, b in zip(ns, bits)]
+    ys = [torch.empty_like(x) for x in xs]
+    descs = gact.make_descs(xs, [b[0] for b in bufs], [b[1] for b in bufs], [b[2] for b in bufs], ys,
+                            ns, bits, seeds, dts)
+    ws = torch.empty(gact.gact_multi_workspace_bytes(L), dtype=torch.uint8, device="cuda")
+
+    def fill(round_):
+        host = []
+        for l in range(L):
+            x = syn.draw_numpy(syn.NORMAL if l % 2 else syn.RELU, ns[l], 900 + 10 * round_ + l)
+            if dts[l] == torch.bfloat16:
+                x = syn.f32_to_bf16_bits(x)
+            xs[l].copy_(to_device(x))
+            host.append(x)
+        return host
+
+    side = torch.cuda.Stream()                       # default priority
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                    # warm-up outside the capture
+        fill(0)
+        gact.gact_compress_multi(descs, L, G, ws)
+        gact.gact_decompress_multi(descs, L, G, ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        gact.gact_compress_multi(descs, L, G, ws)
+        gact.gact_decompress_multi(descs, L, G, ws)
+    for round_ in (1, 2, 3):
+        host = fill(round_)                          # eager copies between the replays
+        for b in bufs:
+            b[0].fill_(CANARY)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for l in range(L):
+            p_ref, mn_ref, sc_ref = oracle.compress(host[l], G, bits[l], seeds[l])
+            dt = oracle.BF16 if host[l].dtype == np.uint16 else oracle.F32
+            y_ref = oracle.decompress(p_ref, mn_ref, sc_ref, ns[l], G, bits[l], dt)
+            assert np.array_equal(to_host(bufs[l][0])[:p_ref.size], p_ref), (round_, l)
+            assert np.array_equal(to_host(bufs[l][1]).view(np.uint32), mn_ref.view(np.uint32)), (round_, l)
+            assert np.array_equal(to_host(bufs[l][2]).view(np.uint32), sc_ref.view(np.uint32)), (round_, l)
+            yh = to_host(ys[l])
+            assert np.array_equal(yh.view(np.uint32) if dt == oracle.F32 else yh,
+                                  y_ref.view(np.uint32) if dt == oracle.F32 else y_ref), (round_, l)
+
+
+def test_a_table_upload_is_refused_on_a_capturing_stream(gact):
+    """More than 64 tensors need their table uploaded from host memory, which a
+    graph replay could not repeat: under capture the call enqueues nothing and
+    says so; the same call works once the capture has ended."""
+    G, L = 128, 70
+    xs = [torch.from_numpy(syn.draw_numpy(syn.NORMAL, 4096, 700 + l)).cuda() for l in range(L)]
+    bufs = [gact.alloc_compressed(4096, G, 4, "cuda") for _ in range(L)]
+    ys = [torch.empty_like(x) for x in xs]
+    descs = gact.make_descs(xs, [b[0] for b in bufs], [b[1] for b in bufs], [b[2] for b in bufs], ys,
+                            [4096] * L, [4] * L, list(range(L)), [torch.float32] * L)
+    ws = torch.empty(gact.gact_multi_workspace_bytes(L), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    codes = []
+    with torch.cuda.graph(graph):
+        for call in (gact.gact_compress_multi, gact.gact_decompress_multi):
+            try:
+                call(descs, L, G, ws)
+                codes.append(0)
+            except gact.GactError as e:
+                codes.append(e.code)
+    assert codes == [gact.GACT_E_CAPTURE, gact.GACT_E_CAPTURE]
+    gact.gact_compress_multi(descs, L, G, ws)
+    gact.gact_decompress_multi(descs, L, G, ws)
+    torch.cuda.synchronize()
+    p_ref, mn_ref, sc_ref = oracle.compress(xs[69].cpu().numpy(), G, 4, 69)
+    assert np.array_equal(to_host(bufs[69][0]), p_ref)
+    assert np.array_equal(ys[69].cpu().numpy(), oracle.decompress(p_ref, mn_ref, sc_ref, 4096, G, 4))
