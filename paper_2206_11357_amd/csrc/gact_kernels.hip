@@ -54,11 +54,6 @@ __device__ __forceinline__ int64_t packed_words(const TensorArgs& t) {
 }
 
 // ---------------------------------------------------------------- lane moves
-template <int CTRL>
-__device__ __forceinline__ float dpp(float v) {
-    return __builtin_bit_cast(
-        float, __builtin_amdgcn_mov_dpp(__builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
 __device__ __forceinline__ float swizzle_xor16(float v) {
     // bit-mask mode: and 0x1f, or 0, xor 0x10 (lane ^ 16 inside each half wave)
     return __builtin_bit_cast(
