@@ -4,6 +4,7 @@ allocator) agree with the oracle.  No kernel is launched here."""
 import ctypes
 import os
 import re
+import sys
 
 import numpy as np
 import pytest
@@ -163,3 +164,13 @@ def test_level_set_allocator_errors():
         with pytest.raises(gact.GactError) as e:
             gact.gact_allocate_bits_levels(c, D, avg, levels)
         assert e.value.code == code
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The path has no cross-GPU step; bench.py says so instead of running."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 2
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
