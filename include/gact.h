@@ -217,6 +217,24 @@ int gact_footprint(const void *d_x, gact_dtype dtype, int64_t n, int n_samples, 
                    void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Compressor and footprint from one read of the tensor: the sum is taken in
+ * the pass that computes the group statistics (Sec. 5.2 names the footprint,
+ * App. A.4 the statistics).  Arguments and results of gact_compress, plus
+ *   d_footprint  out  double[1 + n_samples], as gact_footprint defines it
+ *                     (the sum is accumulated in another fixed order, so it
+ *                     may differ from gact_footprint's in the last bits)
+ *   d_workspace       >= gact_compress_footprint_workspace_bytes(n, group_size)
+ *                     bytes, 16-byte aligned, in use until the kernels have run
+ * A caller that finds the footprint among tensors it already holds drops the
+ * new compressed copy and keeps the old one.  n == 0 writes zeros.
+ */
+size_t gact_compress_footprint_workspace_bytes(int64_t n, int group_size);
+int gact_compress_footprint(const void *d_x, gact_dtype dtype, int64_t n, int group_size,
+                            int bits, uint64_t seed, void *d_packed, float *d_gmin,
+                            float *d_gscale, int n_samples, double *d_footprint,
+                            void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Variance alert (host only): V(b) = sum_l c_l S(b_l) (Thm. 2) against the
  * gradient variance.  Writes V / grad_var to *h_ratio (may be NULL) and
  * returns 1 if it exceeds `threshold`, 0 if not, a negative code on error.

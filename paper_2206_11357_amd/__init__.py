@@ -33,7 +33,8 @@ EXPORTS = (
     "gact_decompress", "gact_multi_workspace_bytes", "gact_compress_multi",
     "gact_decompress_multi", "gact_allocate_bits", "gact_reduce_workspace_bytes",
     "gact_sensitivity", "gact_grad_stats_update", "gact_variance_alert",
-    "gact_allocate_bits_levels", "gact_footprint",
+    "gact_allocate_bits_levels", "gact_footprint", "gact_compress_footprint",
+    "gact_compress_footprint_workspace_bytes",
 )
 GACT_BITS_UNCOMPRESSED = 32
 
@@ -98,6 +99,11 @@ def _load() -> ctypes.CDLL:
     lib.gact_grad_stats_update.restype = i32
     lib.gact_footprint.argtypes = [vp, i32, i64, i32, vp, vp, sz, vp]
     lib.gact_footprint.restype = i32
+    lib.gact_compress_footprint_workspace_bytes.argtypes = [i64, i32]
+    lib.gact_compress_footprint_workspace_bytes.restype = sz
+    lib.gact_compress_footprint.argtypes = [vp, i32, i64, i32, i32, ctypes.c_uint64, vp, vp, vp, i32, vp,
+                                            vp, sz, vp]
+    lib.gact_compress_footprint.restype = i32
     lib.gact_variance_alert.argtypes = [vp, vp, i32, ctypes.c_double, ctypes.c_double, vp]
     lib.gact_variance_alert.restype = i32
     return lib
@@ -338,6 +344,34 @@ def gact_footprint(x: torch.Tensor, n_samples: int = 8, out: Optional[torch.Tens
     if rc != GACT_OK:
         raise GactError(rc, "gact_footprint")
     return out
+
+
+def gact_compress_footprint_workspace_bytes(n: int, group_size: int) -> int:
+    return int(lib.gact_compress_footprint_workspace_bytes(int(n), int(group_size)))
+
+
+def gact_compress_footprint(x: torch.Tensor, group_size: int, bits: int, seed: int, n_samples: int = 8,
+                            packed: Optional[torch.Tensor] = None, gmin: Optional[torch.Tensor] = None,
+                            gscale: Optional[torch.Tensor] = None, footprint: Optional[torch.Tensor] = None,
+                            workspace: Optional[torch.Tensor] = None, stream=None):
+    """Compress one tensor and take its footprint in the same read;
+    returns (packed, gmin, gscale, footprint float64[1 + n_samples])."""
+    x = _flat(x)
+    n = x.numel()
+    if packed is None:
+        packed, gmin, gscale = alloc_compressed(n, max(group_size, 1), bits if bits > 0 else 1, x.device)
+    if footprint is None:
+        footprint = torch.empty(1 + n_samples, dtype=torch.float64, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(gact_compress_footprint_workspace_bytes(n, group_size), 16),
+                                dtype=torch.uint8, device=x.device)
+    rc = lib.gact_compress_footprint(x.data_ptr(), dtype_code(x.dtype), n, group_size, bits,
+                                     seed & (2**64 - 1), packed.data_ptr(), gmin.data_ptr(),
+                                     gscale.data_ptr(), n_samples, footprint.data_ptr(),
+                                     workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if rc != GACT_OK:
+        raise GactError(rc, "gact_compress_footprint")
+    return packed, gmin, gscale, footprint
 
 
 def gact_variance_alert(sensitivity, bits, grad_var: float, threshold: float):

@@ -350,6 +350,38 @@ int gact_footprint(const void* d_x, gact_dtype dtype, int64_t n, int n_samples, 
                                  stream) == 0 ? GACT_OK : GACT_E_HIP;
 }
 
+size_t gact_compress_footprint_workspace_bytes(int64_t n, int group_size) {
+    if (n <= 0 || !group_ok(group_size)) return 0;
+    return (size_t)tiles_for(n, make_geometry(group_size)) * sizeof(double);
+}
+
+int gact_compress_footprint(const void* d_x, gact_dtype dtype, int64_t n, int group_size, int bits,
+                            uint64_t seed, void* d_packed, float* d_gmin, float* d_gscale,
+                            int n_samples, double* d_footprint, void* d_workspace,
+                            size_t workspace_bytes, void* stream) {
+    if (!bits_ok(bits)) return GACT_E_BITS;
+    if (!group_ok(group_size)) return GACT_E_GROUP;
+    if (n_samples < 0 || n_samples > 32768 || !d_footprint || !aligned(d_footprint, 8)) return GACT_E_ARG;
+    gact::Geometry geo = make_geometry(group_size);
+    geo.lds_wave_dwords = gact::lds_dwords_per_wave((int)dtype);
+    gact::TensorArgs t;
+    const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, bits,
+                             (int)dtype, geo, &t);
+    if (rc != GACT_OK) return rc;
+    if (n == 0)
+        return gact_launch_zero(d_footprint, 1 + n_samples, stream) == 0 ? GACT_OK : GACT_E_HIP;
+    if (!d_workspace || !aligned(d_workspace, 16) ||
+        workspace_bytes < gact_compress_footprint_workspace_bytes(n, group_size))
+        return GACT_E_ARG;
+    const int64_t blocks = blocks_for(true, t);
+    if (blocks > 0x7FFFFFFFll) return GACT_E_ARG;
+    if (gact_launch_compress_sum(&t, &geo, (unsigned)blocks, (double*)d_workspace, stream) != 0)
+        return GACT_E_HIP;
+    const gact::ReduceArgs r{d_x, nullptr, n, (int32_t)dtype, 0};
+    return gact_launch_footprint_finish(&r, t.tiles, (double*)d_workspace, n_samples, d_footprint,
+                                        stream) == 0 ? GACT_OK : GACT_E_HIP;
+}
+
 int gact_variance_alert(const float* h_sensitivity, const int32_t* h_bits, int L, double grad_var,
                         double threshold, double* h_ratio) {
     if (L < 0 || (L > 0 && (!h_sensitivity || !h_bits)) || !(grad_var > 0.0)) return GACT_E_ARG;

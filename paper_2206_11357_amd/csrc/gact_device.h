@@ -90,6 +90,10 @@ extern "C" int gact_launch_single(int compress, const gact::TensorArgs* t,
 extern "C" int gact_launch_diff_sq(const gact::ReduceArgs* d_table, const uint32_t* d_first, int K,
                                    unsigned blocks, double* d_partial, double scale, double* d_out,
                                    void* stream);
+extern "C" int gact_launch_compress_sum(const gact::TensorArgs* t, const gact::Geometry* geo,
+                                        unsigned blocks, double* d_tile_sum, void* stream);
+extern "C" int gact_launch_footprint_finish(const gact::ReduceArgs* r, unsigned count, double* d_partial,
+                                            int n_samples, double* d_out, void* stream);
 extern "C" int gact_launch_footprint(const gact::ReduceArgs* r, unsigned blocks, double* d_partial,
                                      int n_samples, double* d_out, void* stream);
 extern "C" int gact_launch_zero(double* d_out, int nout, void* stream);

@@ -279,9 +279,12 @@ __device__ __forceinline__ void wave_lds_sync() {
 // One wavefront compresses tile `tile` of tensor `t`.
 //   geo.lpg        lanes per group (G/32)
 //   geo.lanes_used lanes that hold data in a full tile (64 for power-of-two G)
-template <int DT, int BITS, bool EDGE>
+//   SUM            also write the binary64 sum of the tile's elements to tile_sum[tile]
+//                  (the footprint of Sec. 5.2 from the same read)
+template <int DT, int BITS, bool EDGE, bool SUM>
 __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometry& geo,
-                                              int64_t tile, uint32_t* __restrict__ lds, int lane) {
+                                              int64_t tile, uint32_t* __restrict__ lds, int lane,
+                                              double* __restrict__ tile_sum) {
     constexpr uint32_t B = (1u << BITS) - 1u;
     const int tile_elems = geo.lanes_used * kPerLane;
     const int64_t e0 = tile * (int64_t)tile_elems;
@@ -300,8 +303,19 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
     wave_lds_sync();
     read_row<DT>(lds, lane, v);
 
-    // group statistics
     const int my0 = lane * kPerLane;                 // first element of this lane in the tile
+    if (SUM) {
+        // lane: its 32 elements in index order; wavefront: xor butterfly 32, 16, ... 1
+        double acc = 0.0;
+#pragma unroll
+        for (int j = 0; j < kPerLane; ++j)
+            if (!EDGE || my0 + j < ne) acc += (double)v[j];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+        if (lane == 0) tile_sum[tile] = acc;
+    }
+
+    // group statistics
     float mn, mx;
     if (!EDGE) {
         mn = v[0]; mx = v[0];
@@ -535,8 +549,9 @@ __device__ __forceinline__ void decompress_units(const TensorArgs& t, const Geom
         default: break;                                                              \
     }
 
+template <bool SUM>
 __device__ __forceinline__ void compress_block(const TensorArgs& t, const Geometry& geo,
-                                               int64_t block_in_tensor) {
+                                               int64_t block_in_tensor, double* __restrict__ tile_sum) {
     // sized by the launcher: geo.lds_wave_dwords per wavefront
     extern __shared__ __attribute__((aligned(16))) uint32_t lds_all[];
     const int wave = threadIdx.x >> 6;
@@ -546,8 +561,8 @@ __device__ __forceinline__ void compress_block(const TensorArgs& t, const Geomet
     if (tile >= (int64_t)t.tiles) return;
     // a tile is "full" when all its elements exist and G is a power of two
     const bool full = geo.pow2 && (tile + 1) * (int64_t)(geo.lanes_used * kPerLane) <= t.n;
-#define GACT_C_FULL(DT, BITS) compress_tile<DT, BITS, false>(t, geo, tile, lds, lane);
-#define GACT_C_EDGE(DT, BITS) compress_tile<DT, BITS, true>(t, geo, tile, lds, lane);
+#define GACT_C_FULL(DT, BITS) compress_tile<DT, BITS, false, SUM>(t, geo, tile, lds, lane, tile_sum);
+#define GACT_C_EDGE(DT, BITS) compress_tile<DT, BITS, true, SUM>(t, geo, tile, lds, lane, tile_sum);
     if (full) { GACT_DISPATCH(t, GACT_C_FULL) } else { GACT_DISPATCH(t, GACT_C_EDGE) }
 #undef GACT_C_FULL
 #undef GACT_C_EDGE
@@ -571,13 +586,19 @@ __device__ __forceinline__ void decompress_block(const TensorArgs& t, const Geom
 template <bool COMPRESS>
 __device__ __forceinline__ void run_block(const TensorArgs& t, const Geometry& geo,
                                           int64_t block_in_tensor) {
-    if (COMPRESS) compress_block(t, geo, block_in_tensor);
+    if (COMPRESS) compress_block<false>(t, geo, block_in_tensor, nullptr);
     else decompress_block(t, geo, block_in_tensor);
 }
 
 template <bool COMPRESS>
 __global__ __launch_bounds__(kBlockThreads) void single_kernel(TensorArgs t, Geometry geo) {
     run_block<COMPRESS>(t, geo, (int64_t)blockIdx.x);
+}
+
+// One tensor, compressed, with the sum of every tile as a by-product.
+__global__ __launch_bounds__(kBlockThreads) void compress_sum_kernel(TensorArgs t, Geometry geo,
+                                                                     double* __restrict__ tile_sum) {
+    compress_block<true>(t, geo, (int64_t)blockIdx.x, tile_sum);
 }
 
 // Multi-tensor: block b belongs to the tensor l with first_block[l] <= b <
@@ -622,6 +643,14 @@ extern "C" int gact_launch_single(int compress, const gact::TensorArgs* t, const
         hipLaunchKernelGGL(gact::single_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), lds, s, *t, *geo);
     else
         hipLaunchKernelGGL(gact::single_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), lds, s, *t, *geo);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+extern "C" int gact_launch_compress_sum(const gact::TensorArgs* t, const gact::Geometry* geo,
+                                        unsigned blocks, double* d_tile_sum, void* stream) {
+    const unsigned lds = 4u * gact::kWavesPerBlk * (unsigned)geo->lds_wave_dwords;
+    hipLaunchKernelGGL(gact::compress_sum_kernel, dim3(blocks), dim3(gact::kBlockThreads), lds,
+                       (hipStream_t)stream, *t, *geo, d_tile_sum);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 

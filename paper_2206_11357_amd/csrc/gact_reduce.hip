@@ -305,6 +305,18 @@ extern "C" int gact_launch_zero(double* d_out, int nout, void* stream) {
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+// The footprint from per-tile sums that a compress launch left in d_partial.
+extern "C" int gact_launch_footprint_finish(const gact::ReduceArgs* r, unsigned count, double* d_partial,
+                                            int n_samples, double* d_out, void* stream) {
+    hipStream_t s = (hipStream_t)stream;
+    hipLaunchKernelGGL(gact::finish_kernel, dim3(1), dim3(gact::kFinThreads), 0, s, d_partial, count,
+                       1.0, d_out);
+    if (n_samples > 0)
+        hipLaunchKernelGGL(gact::sample_kernel, dim3((n_samples + 255) / 256), dim3(256), 0, s, *r,
+                           n_samples, d_out);
+    return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 extern "C" int gact_launch_footprint(const gact::ReduceArgs* r, unsigned blocks, double* d_partial,
                                      int n_samples, double* d_out, void* stream) {
     hipStream_t s = (hipStream_t)stream;

@@ -16,8 +16,8 @@ from typing import Callable, Dict, List, Optional, Sequence
 import numpy as np
 import torch
 
-from . import (GACT_BITS_UNCOMPRESSED, gact_allocate_bits_levels, gact_compress, gact_decompress,
-               gact_footprint, gact_sensitivity)
+from . import (GACT_BITS_UNCOMPRESSED, gact_allocate_bits_levels, gact_compress, gact_compress_footprint,
+               gact_decompress, gact_sensitivity)
 
 
 @dataclass
@@ -49,7 +49,7 @@ class Controller:
         # dedup: a tensor saved by several operators is compressed once.  The data pointer
         # alone cannot identify it (the allocator hands a freed activation's address to the
         # next one), so candidates are confirmed by their footprint: sum + sampled points
-        # (Sec. 5.2).  Costs one extra read of every saved tensor.
+        # (Sec. 5.2), taken by the compressor in the same read; a duplicate's new copy is dropped.
         self.dedup = dedup
         self.param_ptrs = {p.data_ptr() for p in params}
         self.bits: Dict[int, int] = {}            # index l -> b_l
@@ -82,19 +82,24 @@ class Controller:
     def pack(self, x: torch.Tensor):
         if not self._eligible(x):
             return x
-        key = (x.data_ptr(), x.numel(), x.dtype)
-        fp = gact_footprint(x.detach(), 8) if self.dedup else None
-        if self.dedup and key in self._by_storage:
-            h, old_fp = self._by_storage[key]
-            if torch.equal(fp, old_fp):
-                return h                             # saved before in this iteration: share it
         index = self._index
-        self._index += 1
-        self.numel.append(x.numel())
         b = self.bits_of(index)
         if b == GACT_BITS_UNCOMPRESSED:
+            self._index += 1
+            self.numel.append(x.numel())
             return x
-        packed, gmin, gscale = gact_compress(x.detach(), self.group_size, b, self.seed_of(index))
+        if self.dedup:
+            # one read: the sum is taken in the compressor's statistics pass
+            packed, gmin, gscale, fp = gact_compress_footprint(x.detach(), self.group_size, b,
+                                                               self.seed_of(index), 8)
+            key = (x.data_ptr(), x.numel(), x.dtype)
+            hit = self._by_storage.get(key)
+            if hit is not None and torch.equal(fp, hit[1]):
+                return hit[0]                        # saved before in this iteration: share it, drop the new copy
+        else:
+            packed, gmin, gscale = gact_compress(x.detach(), self.group_size, b, self.seed_of(index))
+        self._index += 1
+        self.numel.append(x.numel())
         h = _Packed(index, x.shape, x.dtype, x.numel(), b, packed, gmin, gscale)
         if self.swap:
             self._swap_out(h)

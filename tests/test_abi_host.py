@@ -62,6 +62,25 @@ def test_argument_errors_are_reported_before_any_launch():
         rc = lib.gact_decompress(a["packed"], a["gmin"], a["gscale"], a["n"], a["G"], a["bits"],
                                  a["x"], a["dt"], None)
         assert rc == want, (over, rc)
+        rc = lib.gact_compress_footprint(a["x"], a["dt"], a["n"], a["G"], a["bits"], 0, a["packed"],
+                                         a["gmin"], a["gscale"], 4, p16 + 3584, p16 + 3328, 64, None)
+        assert rc == want, (over, rc)
+    # the fused call's own arguments: sample count, footprint pointer, workspace
+    ok = dict(x=p16, dt=0, n=64, G=32, bits=2, packed=p16 + 1024, gmin=p16 + 2048, gscale=p16 + 3072)
+    fused = lambda ns, fp, ws, wsb: lib.gact_compress_footprint(
+        ok["x"], ok["dt"], ok["n"], ok["G"], ok["bits"], 0, ok["packed"], ok["gmin"], ok["gscale"],
+        ns, fp, ws, wsb, None)
+    assert fused(-1, p16 + 3584, p16 + 3328, 64) == gact.GACT_E_ARG
+    assert fused(32769, p16 + 3584, p16 + 3328, 64) == gact.GACT_E_ARG
+    assert fused(4, 0, p16 + 3328, 64) == gact.GACT_E_ARG
+    assert fused(4, p16 + 3584 + 4, p16 + 3328, 64) == gact.GACT_E_ARG                   # misaligned
+    assert fused(4, p16 + 3584, 0, 64) == gact.GACT_E_ARG                                # no workspace
+    assert fused(4, p16 + 3584, p16 + 3328, 4) == gact.GACT_E_ARG                        # too small
+    assert gact.gact_compress_footprint_workspace_bytes(64, 32) == 8
+    assert gact.gact_compress_footprint_workspace_bytes(2049, 256) == 16
+    assert gact.gact_compress_footprint_workspace_bytes(63 * 32 + 1, 96) == 16           # 63 lanes per tile
+    assert gact.gact_compress_footprint_workspace_bytes(0, 256) == 0
+    assert gact.gact_compress_footprint_workspace_bytes(100, 48) == 0
     # n == 0 succeeds without touching anything
     assert lib.gact_compress(None, 0, 0, 32, 2, 0, None, None, None, None) == gact.GACT_OK
     assert lib.gact_decompress(None, None, None, 0, 32, 2, None, 0, None) == gact.GACT_OK

@@ -145,3 +145,32 @@ def test_footprint_matches_the_oracle(gact, dtype):
     assert gact.gact_footprint(e, 4).cpu().numpy().tolist() == [0.0] * 5
     k = torch.arange(1, 1001, dtype=torch.float32, device="cuda")
     assert gact.gact_footprint(k, 4).cpu().numpy().tolist() == [500500.0, 1.0, 251.0, 501.0, 751.0]
+
+
+@pytest.mark.parametrize("dtype", ("f32", "bf16"))
+def test_compress_with_footprint_in_one_pass(gact, dtype):
+    """The fused call returns gact_compress's bytes and gact_footprint's values
+    (the sum in another fixed order: same bar against the oracle)."""
+    cases = [(1, 32, 2), (2047, 256, 1), (2048, 256, 2), (2049, 256, 4), (70001, 128, 8), (100000, 96, 4),
+             (1 << 20, 1024, 2), (5 * 2048 * 4 + 3, 64, 2)]
+    for n, G, bits in cases:
+        x = syn.draw_numpy(syn.RELU if n % 2 else syn.NORMAL, n, n % 97)
+        if dtype == "bf16":
+            x = syn.f32_to_bf16_bits(x)
+        xd = dev(x)
+        for ns in (0, 8):
+            p, mn, sc, fp = gact.gact_compress_footprint(xd, G, bits, 1234 + n, ns)
+            p0, mn0, sc0 = gact.gact_compress(xd, G, bits, 1234 + n)
+            assert torch.equal(p, p0) and torch.equal(mn, mn0) and torch.equal(sc, sc0), (n, G, bits)
+            p_ref, mn_ref, sc_ref = oracle.compress(x, G, bits, 1234 + n)
+            assert np.array_equal(p.cpu().numpy(), p_ref)
+            want = oracle.footprint(x, ns)
+            got = fp.cpu().numpy()
+            mag = float(np.sum(np.abs(syn.bf16_bits_to_f32(x) if dtype == "bf16" else x).astype(np.float64)))
+            assert abs(got[0] - want[0]) <= REL * mag, (n, G, bits)
+            assert np.array_equal(got[1:], want[1:])
+    e = torch.empty(0, device="cuda")
+    out = gact.gact_compress_footprint(e, 256, 2, 0, 4)
+    assert out[3].cpu().numpy().tolist() == [0.0] * 5
+    k = torch.arange(1, 1001, dtype=torch.float32, device="cuda")
+    assert gact.gact_compress_footprint(k, 32, 4, 0, 4)[3].cpu().numpy().tolist() == [500500.0, 1.0, 251.0, 501.0, 751.0]
