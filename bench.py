@@ -211,10 +211,12 @@ def main() -> int:
             "input_bytes": in_bytes, "algorithmic_bytes_per_direction": alg_bytes,
             "launch": "one multi-tensor launch per direction",
         },
-        "compress": {"ms": round(c_avg, 4), "input_GBps": round(in_bytes / c_avg / 1e6, 1),
+        "compress": {"ms": round(c_avg, 4), "ms_median": round(float(np.median(c_ms)), 4),
+                     "ms_min": round(float(np.min(c_ms)), 4), "input_GBps": round(in_bytes / c_avg / 1e6, 1),
                      "elements_per_s": round(n_total / c_avg * 1e3, 0),
                      "pct_hbm_peak": round(100 * alg_bytes / c_avg / 1e6 / HBM_PEAK_GBPS, 2)},
-        "decompress": {"ms": round(d_avg, 4), "input_GBps": round(in_bytes / d_avg / 1e6, 1),
+        "decompress": {"ms": round(d_avg, 4), "ms_median": round(float(np.median(d_ms)), 4),
+                       "ms_min": round(float(np.min(d_ms)), 4), "input_GBps": round(in_bytes / d_avg / 1e6, 1),
                        "elements_per_s": round(n_total / d_avg * 1e3, 0),
                        "pct_hbm_peak": round(100 * alg_bytes / d_avg / 1e6 / HBM_PEAK_GBPS, 2)},
         "fused_pct_hbm_peak": round(100 * 2 * alg_bytes / (c_avg + d_avg) / 1e6 / HBM_PEAK_GBPS, 2),
