@@ -415,3 +415,34 @@ def test_a_table_upload_is_refused_on_a_capturing_stream(gact):
     p_ref, mn_ref, sc_ref = oracle.compress(xs[69].cpu().numpy(), G, 4, 69)
     assert np.array_equal(to_host(bufs[69][0]), p_ref)
     assert np.array_equal(ys[69].cpu().numpy(), oracle.decompress(p_ref, mn_ref, sc_ref, 4096, G, 4))
+
+
+def test_calls_on_two_streams_do_not_interfere(gact):
+    """The library keeps no state between calls: launches enqueued on two
+    streams at the same time (each with its own buffers and workspace) give the
+    oracle's bytes."""
+    G = 256
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]          # default priority
+    jobs = []
+    for k, s in enumerate(streams):
+        x_np = [syn.draw_numpy(syn.NORMAL, 300000 + 4097 * k, 40 + k), syn.draw_numpy(syn.RELU, 8192 * 30, 50 + k)]
+        bits = [2 + 2 * k, 1 + 7 * k]
+        with torch.cuda.stream(s):
+            xs = [to_device(x) for x in x_np]
+            bufs = [gact.alloc_compressed(x.size, G, b, "cuda") for x, b in zip(x_np, bits)]
+            ys = [torch.empty_like(x) for x in xs]
+            descs = gact.make_descs(xs, [b[0] for b in bufs], [b[1] for b in bufs], [b[2] for b in bufs], ys,
+                                    [x.size for x in x_np], bits, [k, k + 10], [torch.float32] * 2)
+            ws = torch.empty(gact.gact_multi_workspace_bytes(2), dtype=torch.uint8, device="cuda")
+        jobs.append((s, x_np, bits, xs, bufs, ys, descs, ws))
+    for _ in range(5):                                             # interleave the launches
+        for s, x_np, bits, xs, bufs, ys, descs, ws in jobs:
+            with torch.cuda.stream(s):
+                gact.gact_compress_multi(descs, 2, G, ws)
+                gact.gact_decompress_multi(descs, 2, G, ws)
+    torch.cuda.synchronize()
+    for k, (s, x_np, bits, xs, bufs, ys, descs, ws) in enumerate(jobs):
+        for l in range(2):
+            p_ref, mn_ref, sc_ref = oracle.compress(x_np[l], G, bits[l], k + 10 * l)
+            assert np.array_equal(to_host(bufs[l][0]), p_ref), (k, l)
+            assert np.array_equal(to_host(ys[l]), oracle.decompress(p_ref, mn_ref, sc_ref, x_np[l].size, G, bits[l])), (k, l)
