@@ -1,8 +1,8 @@
 """Saved-tensor hooks that route autograd's saved activations through the GACT
 compressor (arXiv 2206.11357, Sec. 5: one hook interface for all operators;
 Sec. 5.2: parameters and tensors that need no gradient are not quantized;
-Sec. 5.3: optional swap of the *compressed* tensors to host memory on side
-streams, with prefetch during the backward pass).
+Sec. 5.3: optional swap of the *compressed* tensors to host memory on two side
+streams (one out, one in), with prefetch during the backward pass).
 
 This is glue around the library's kernels: ``pack`` calls ``gact_compress``,
 ``unpack`` calls ``gact_decompress``.  Per-tensor bit widths and the
@@ -59,7 +59,9 @@ class Controller:
         self._index = 0
         self._live: Dict[int, _Packed] = {}
         self._by_storage: Dict[tuple, tuple] = {}   # (ptr, numel, dtype) -> (handle, footprint)
-        self._side = torch.cuda.Stream() if swap else None     # default priority
+        # swap-out and swap-in each on a stream of their own (Sec. 5.3), both at default priority
+        self._out_stream = torch.cuda.Stream() if swap else None
+        self._in_stream = torch.cuda.Stream() if swap else None
 
     # ------------------------------------------------------------- iteration
     def begin_iteration(self) -> None:
@@ -128,13 +130,13 @@ class Controller:
     def _swap_out(self, h: _Packed) -> None:
         done = torch.cuda.Event()
         done.record()                                   # compression finished on the main stream
-        with torch.cuda.stream(self._side):
-            self._side.wait_event(done)
+        with torch.cuda.stream(self._out_stream):
+            self._out_stream.wait_event(done)
             host = []
             for t in (h.packed, h.gmin, h.gscale):
                 buf = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
                 buf.copy_(t, non_blocking=True)
-                t.record_stream(self._side)
+                t.record_stream(self._out_stream)
                 host.append(buf)
             h.out_event = torch.cuda.Event()
             h.out_event.record()
@@ -143,8 +145,8 @@ class Controller:
 
     def _start_swap_in(self, h: _Packed) -> None:
         main = torch.cuda.current_stream()
-        with torch.cuda.stream(self._side):
-            self._side.wait_event(h.out_event)
+        with torch.cuda.stream(self._in_stream):
+            self._in_stream.wait_event(h.out_event)
             dev = []
             for buf in h.host:
                 t = torch.empty(buf.shape, dtype=buf.dtype, device="cuda")
