@@ -17,7 +17,7 @@ import numpy as np
 import torch
 
 from . import (GACT_BITS_UNCOMPRESSED, gact_allocate_bits_levels, gact_compress, gact_compress_footprint,
-               gact_decompress, gact_sensitivity)
+               gact_decompress, gact_num_groups, gact_packed_bytes, gact_sensitivity)
 
 
 @dataclass
@@ -30,7 +30,8 @@ class _Packed:
     packed: Optional[torch.Tensor]
     gmin: Optional[torch.Tensor]
     gscale: Optional[torch.Tensor]
-    host: Optional[tuple] = None          # pinned copies when swapped out
+    blob: Optional[torch.Tensor] = None   # swap mode: the one device buffer the three above are views of
+    host: Optional[torch.Tensor] = None   # pinned copy of the blob when swapped out
     out_event: Optional[torch.cuda.Event] = None
     in_event: Optional[torch.cuda.Event] = None
 
@@ -62,9 +63,17 @@ class Controller:
         # swap-out and swap-in each on a stream of their own (Sec. 5.3), both at default priority
         self._out_stream = torch.cuda.Stream() if swap else None
         self._in_stream = torch.cuda.Stream() if swap else None
+        # pinned host memory for the swapped tensors: one arena, handed out front to back within
+        # an iteration (a pinned allocation per tensor costs more than the copy it serves)
+        self._arena: Optional[torch.Tensor] = None
+        self._arena_used = 0
 
     # ------------------------------------------------------------- iteration
     def begin_iteration(self) -> None:
+        # The arena is reused from its start: the copies that read it in the last backward
+        # pass were waited for by the main stream, which orders them before this iteration's
+        # swap-outs (those wait for an event the main stream records after compressing).
+        self._arena_used = 0
         self._index = 0
         self._live.clear()
         self._by_storage.clear()
@@ -90,19 +99,24 @@ class Controller:
             self._index += 1
             self.numel.append(x.numel())
             return x
+        blob, out = None, (None, None, None)
+        if self.swap:
+            # packed codes, minima and steps in one buffer, so that a swap is one copy each way
+            blob = torch.empty(self._blob_bytes(x.numel(), b), dtype=torch.uint8, device=x.device)
+            out = self._views(blob, x.numel(), b)
         if self.dedup:
             # one read: the sum is taken in the compressor's statistics pass
             packed, gmin, gscale, fp = gact_compress_footprint(x.detach(), self.group_size, b,
-                                                               self.seed_of(index), 8)
+                                                               self.seed_of(index), 8, *out)
             key = (x.data_ptr(), x.numel(), x.dtype)
             hit = self._by_storage.get(key)
             if hit is not None and torch.equal(fp, hit[1]):
                 return hit[0]                        # saved before in this iteration: share it, drop the new copy
         else:
-            packed, gmin, gscale = gact_compress(x.detach(), self.group_size, b, self.seed_of(index))
+            packed, gmin, gscale = gact_compress(x.detach(), self.group_size, b, self.seed_of(index), *out)
         self._index += 1
         self.numel.append(x.numel())
-        h = _Packed(index, x.shape, x.dtype, x.numel(), b, packed, gmin, gscale)
+        h = _Packed(index, x.shape, x.dtype, x.numel(), b, packed, gmin, gscale, blob)
         if self.swap:
             self._swap_out(h)
         self._live[index] = h
@@ -127,35 +141,51 @@ class Controller:
         return torch.autograd.graph.saved_tensors_hooks(self.pack, self.unpack)
 
     # ------------------------------------------------------------------- swap
+    def _pinned(self, like: torch.Tensor) -> torch.Tensor:
+        """A pinned host buffer shaped like `like`, cut from the arena."""
+        nbytes = like.numel() * like.element_size()
+        start = (self._arena_used + 255) & ~255
+        if self._arena is None or start + nbytes > self._arena.numel():
+            # grow: handles of this iteration keep the old arena's storage alive through their views
+            grown = max(2 * (self._arena.numel() if self._arena is not None else 0), nbytes, 64 << 20)
+            self._arena = torch.empty(grown, dtype=torch.uint8, pin_memory=True)
+            start = 0
+        self._arena_used = start + nbytes
+        return self._arena[start:start + nbytes].view(like.dtype).view(like.shape)
+
+    def _blob_bytes(self, n: int, bits: int) -> int:
+        return gact_packed_bytes(n, bits) + 8 * gact_num_groups(n, self.group_size)
+
+    def _views(self, blob: torch.Tensor, n: int, bits: int):
+        """(packed, gmin, gscale) inside `blob`; the packed size is a multiple of 16 bytes."""
+        pb, ng = gact_packed_bytes(n, bits), gact_num_groups(n, self.group_size)
+        return (blob[:pb], blob[pb:pb + 4 * ng].view(torch.float32),
+                blob[pb + 4 * ng:pb + 8 * ng].view(torch.float32))
+
     def _swap_out(self, h: _Packed) -> None:
         done = torch.cuda.Event()
         done.record()                                   # compression finished on the main stream
+        buf = self._pinned(h.blob)
         with torch.cuda.stream(self._out_stream):
             self._out_stream.wait_event(done)
-            host = []
-            for t in (h.packed, h.gmin, h.gscale):
-                buf = torch.empty(t.shape, dtype=t.dtype, pin_memory=True)
-                buf.copy_(t, non_blocking=True)
-                t.record_stream(self._out_stream)
-                host.append(buf)
+            buf.copy_(h.blob, non_blocking=True)
+            h.blob.record_stream(self._out_stream)
             h.out_event = torch.cuda.Event()
             h.out_event.record()
-        h.host = tuple(host)
-        h.packed = h.gmin = h.gscale = None             # device copies may be reused once copied
+        h.host = buf
+        h.blob = h.packed = h.gmin = h.gscale = None    # the device copy may be reused once copied
 
     def _start_swap_in(self, h: _Packed) -> None:
         main = torch.cuda.current_stream()
         with torch.cuda.stream(self._in_stream):
             self._in_stream.wait_event(h.out_event)
-            dev = []
-            for buf in h.host:
-                t = torch.empty(buf.shape, dtype=buf.dtype, device="cuda")
-                t.copy_(buf, non_blocking=True)
-                t.record_stream(main)
-                dev.append(t)
+            blob = torch.empty(h.host.shape, dtype=torch.uint8, device="cuda")
+            blob.copy_(h.host, non_blocking=True)
+            blob.record_stream(main)
             h.in_event = torch.cuda.Event()
             h.in_event.record()
-        h.packed, h.gmin, h.gscale = dev
+        h.blob = blob
+        h.packed, h.gmin, h.gscale = self._views(blob, h.n, h.bits)
 
     def _swap_in(self, h: _Packed) -> None:
         if h.packed is None:
