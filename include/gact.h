@@ -130,6 +130,12 @@ int gact_decompress(const void *d_packed, const float *d_gmin,
  * the node).  A larger table needs an upload from host memory the call owns,
  * which a graph could not replay: on a capturing stream such a call enqueues
  * nothing and returns GACT_E_CAPTURE -- capture those sets in slices of 64.
+ * Shards: the noise of element i is a function of (seed, index_base + i) only,
+ * so a tensor cut at multiples of the group size and compressed piece by piece
+ * (on one GPU or on several), each piece with the tensor's seed and its own
+ * offset as index_base, gives pieces whose packed strings, minima and steps
+ * concatenate to the result for the whole tensor.  index_base must be a
+ * non-negative multiple of 8 (GACT_E_ARG otherwise); decompress ignores it.
  * A descriptor with bits == GACT_BITS_UNCOMPRESSED is skipped by both calls:
  * the allocator left that tensor at full precision and the caller keeps it.
  * L == 0, or all n == 0, is GACT_OK and launches nothing.
@@ -144,6 +150,7 @@ typedef struct {
     uint64_t    seed;
     int32_t     bits;
     int32_t     dtype;     /* gact_dtype */
+    int64_t     index_base; /* compress: index of x[0] in the noise stream (see below); 0 for a whole tensor */
 } gact_tensor_desc;
 
 size_t gact_multi_workspace_bytes(int L);

@@ -49,7 +49,8 @@ class TensorDesc(ctypes.Structure):
     """Mirror of gact_tensor_desc."""
     _fields_ = [("x", ctypes.c_void_p), ("packed", ctypes.c_void_p), ("gmin", ctypes.c_void_p),
                 ("gscale", ctypes.c_void_p), ("y", ctypes.c_void_p), ("n", ctypes.c_int64),
-                ("seed", ctypes.c_uint64), ("bits", ctypes.c_int32), ("dtype", ctypes.c_int32)]
+                ("seed", ctypes.c_uint64), ("bits", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("index_base", ctypes.c_int64)]
 
 
 class GradPair(ctypes.Structure):
@@ -196,8 +197,10 @@ def gact_decompress(packed: torch.Tensor, gmin: torch.Tensor, gscale: torch.Tens
 def make_descs(xs: Sequence[Optional[torch.Tensor]], packed: Sequence[torch.Tensor],
                gmin: Sequence[torch.Tensor], gscale: Sequence[torch.Tensor],
                ys: Sequence[Optional[torch.Tensor]], ns: Sequence[int], bits: Sequence[int],
-               seeds: Sequence[int], dtypes: Sequence[torch.dtype]):
-    """ctypes array of gact_tensor_desc from per-tensor buffers."""
+               seeds: Sequence[int], dtypes: Sequence[torch.dtype],
+               index_bases: Optional[Sequence[int]] = None):
+    """ctypes array of gact_tensor_desc from per-tensor buffers; index_bases gives each
+    entry's offset in its tensor's noise stream when the entries are shards (default 0)."""
     L = len(ns)
     arr = (TensorDesc * max(L, 1))()
     for l in range(L):
@@ -211,6 +214,7 @@ def make_descs(xs: Sequence[Optional[torch.Tensor]], packed: Sequence[torch.Tens
         d.seed = int(seeds[l]) & (2**64 - 1)
         d.bits = int(bits[l])
         d.dtype = dtype_code(dtypes[l])
+        d.index_base = int(index_bases[l]) if index_bases is not None else 0
     return arr
 
 

@@ -43,10 +43,12 @@ int64_t tiles_for(int64_t n, const gact::Geometry& geo) {
 
 // Fills `out`; returns GACT_OK or the error for this tensor.
 int make_args(bool compress, const void* x, void* packed, float* gmin, float* gscale, void* y,
-              int64_t n, uint64_t seed, int bits, int dtype, const gact::Geometry& geo,
-              gact::TensorArgs* out) {
+              int64_t n, uint64_t seed, int64_t index_base, int bits, int dtype,
+              const gact::Geometry& geo, gact::TensorArgs* out) {
     if (!bits_ok(bits)) return GACT_E_BITS;
     if (n < 0 || !dtype_ok(dtype)) return GACT_E_ARG;
+    // noise is drawn per block of 8 elements: a shard starts on a block boundary
+    if (index_base < 0 || (index_base & 7) != 0 || (index_base >> 3) >= (1ll << 48)) return GACT_E_ARG;
     if (n > 0) {
         const void* io = compress ? x : y;
         if (!io || !packed || !gmin || !gscale) return GACT_E_ARG;
@@ -62,22 +64,23 @@ int make_args(bool compress, const void* x, void* packed, float* gmin, float* gs
     out->n = n;
     out->seed_lo = (uint32_t)seed;
     out->seed_hi = (uint32_t)(seed >> 32);
-    out->tiles = (uint32_t)tiles;
-    out->bits_dtype = (uint32_t)bits | ((uint32_t)dtype << 8);
+    const uint64_t blk_base = (uint64_t)index_base >> 3;
+    out->blk_base_lo = (uint32_t)blk_base;
+    out->meta = (uint32_t)bits | ((uint32_t)dtype << 8) | ((uint32_t)(blk_base >> 32) << 16);
     return GACT_OK;
 }
 
 // blocks a tensor needs: compress takes 4 wavefront tiles per block, decompress
 // a fixed span of elements per block
-int64_t blocks_for(bool compress, const gact::TensorArgs& t) {
-    if (compress) return ((int64_t)t.tiles + kWavesPerBlock - 1) / kWavesPerBlock;
+int64_t blocks_for(bool compress, const gact::TensorArgs& t, const gact::Geometry& geo) {
+    if (compress) return (tiles_for(t.n, geo) + kWavesPerBlock - 1) / kWavesPerBlock;
     const int64_t span = gact::dec_block_elems(t.dtype(), t.bits());
     return (t.n + span - 1) / span;
 }
 
 int run_single(bool compress, const gact::TensorArgs& t, const gact::Geometry& geo, void* stream) {
     if (t.n == 0) return GACT_OK;
-    const int64_t blocks = blocks_for(compress, t);
+    const int64_t blocks = blocks_for(compress, t, geo);
     if (blocks > 0x7FFFFFFFll) return GACT_E_ARG;
     return gact_launch_single(compress ? 1 : 0, &t, &geo, (unsigned)blocks, stream) == 0
                ? GACT_OK : GACT_E_HIP;
@@ -116,13 +119,13 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
         }
         gact::TensorArgs t;
         const int rc = make_args(compress, d.x, d.packed, d.gmin, d.gscale, d.y, d.n, d.seed,
-                                 d.bits, d.dtype, geo, &t);
+                                 compress ? d.index_base : 0, d.bits, d.dtype, geo, &t);
         if (rc != GACT_OK) return rc;
         if (d.n == 0) continue;
         first.push_back((uint32_t)blocks);
         table.push_back(t);
         geo.lds_wave_dwords = std::max(geo.lds_wave_dwords, gact::lds_dwords_per_wave(d.dtype));
-        blocks += (uint64_t)blocks_for(compress, t);
+        blocks += (uint64_t)blocks_for(compress, t, geo);
         if (blocks > 0x7FFFFFFFull) return GACT_E_ARG;
     }
     const int live = (int)table.size();
@@ -238,7 +241,7 @@ int gact_compress(const void* d_x, gact_dtype dtype, int64_t n, int group_size, 
     gact::Geometry geo = make_geometry(group_size);
     geo.lds_wave_dwords = gact::lds_dwords_per_wave((int)dtype);
     gact::TensorArgs t;
-    const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, bits,
+    const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, 0, bits,
                              (int)dtype, geo, &t);
     if (rc != GACT_OK) return rc;
     return run_single(true, t, geo, stream);
@@ -251,7 +254,7 @@ int gact_decompress(const void* d_packed, const float* d_gmin, const float* d_gs
     const gact::Geometry geo = make_geometry(group_size);
     gact::TensorArgs t;
     const int rc = make_args(false, nullptr, const_cast<void*>(d_packed),
-                             const_cast<float*>(d_gmin), const_cast<float*>(d_gscale), d_y, n, 0,
+                             const_cast<float*>(d_gmin), const_cast<float*>(d_gscale), d_y, n, 0, 0,
                              bits, (int)dtype, geo, &t);
     if (rc != GACT_OK) return rc;
     return run_single(false, t, geo, stream);
@@ -365,7 +368,7 @@ int gact_compress_footprint(const void* d_x, gact_dtype dtype, int64_t n, int gr
     gact::Geometry geo = make_geometry(group_size);
     geo.lds_wave_dwords = gact::lds_dwords_per_wave((int)dtype);
     gact::TensorArgs t;
-    const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, bits,
+    const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, 0, bits,
                              (int)dtype, geo, &t);
     if (rc != GACT_OK) return rc;
     if (n == 0)
@@ -373,12 +376,12 @@ int gact_compress_footprint(const void* d_x, gact_dtype dtype, int64_t n, int gr
     if (!d_workspace || !aligned(d_workspace, 16) ||
         workspace_bytes < gact_compress_footprint_workspace_bytes(n, group_size))
         return GACT_E_ARG;
-    const int64_t blocks = blocks_for(true, t);
+    const int64_t blocks = blocks_for(true, t, geo);
     if (blocks > 0x7FFFFFFFll) return GACT_E_ARG;
     if (gact_launch_compress_sum(&t, &geo, (unsigned)blocks, (double*)d_workspace, stream) != 0)
         return GACT_E_HIP;
     const gact::ReduceArgs r{d_x, nullptr, n, (int32_t)dtype, 0};
-    return gact_launch_footprint_finish(&r, t.tiles, (double*)d_workspace, n_samples, d_footprint,
+    return gact_launch_footprint_finish(&r, (unsigned)tiles_for(n, geo), (double*)d_workspace, n_samples, d_footprint,
                                         stream) == 0 ? GACT_OK : GACT_E_HIP;
 }
 

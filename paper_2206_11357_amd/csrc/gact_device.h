@@ -23,13 +23,16 @@ struct TensorArgs {
     float*      gscale;    // per-group dequantisation step
     int64_t     n;         // elements
     uint32_t    seed_lo, seed_hi;
-    uint32_t    tiles;     // compress: wavefront tiles covering the tensor
     // Whole dwords only: a sub-dword field would be fetched with a vector load,
     // which queues behind the kernel's own HBM traffic at the start of every block,
     // whereas dword fields of a uniform record come through the scalar cache.
-    uint32_t    bits_dtype;   // bits | dtype << 8
-    __host__ __device__ int bits() const { return (int)(bits_dtype & 0xFFu); }
-    __host__ __device__ int dtype() const { return (int)(bits_dtype >> 8); }
+    uint32_t    blk_base_lo;  // Philox block of element 0 (index_base / 8), low word
+    uint32_t    meta;         // bits | dtype << 8 | (index_base / 8 >> 32) << 16
+    __host__ __device__ int bits() const { return (int)(meta & 0xFFu); }
+    __host__ __device__ int dtype() const { return (int)((meta >> 8) & 0xFFu); }
+    __host__ __device__ uint64_t blk_base() const {
+        return ((uint64_t)(meta >> 16) << 32) | blk_base_lo;
+    }
 };
 
 // How a group size maps onto a wavefront: a lane owns 32 consecutive

@@ -360,7 +360,7 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
 #pragma unroll
     for (int w = 0; w < BITS; ++w) acc[w] = 0u;
     const float ninv17 = -(inv * 0x1p17f);
-    const uint64_t blk0 = (uint64_t)(e0 + my0) >> 3;
+    const uint64_t blk0 = t.blk_base() + ((uint64_t)(e0 + my0) >> 3);
 #pragma unroll
     for (int c = 3; c >= 0; --c) {
         uint32_t r[4];
@@ -412,7 +412,7 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
         // when a tile is narrower than 128*8/BITS elements' worth of padding
         // (group sizes that are not a power of two), up to three pad words lie
         // past the last tile's lanes: the last tile zeroes them
-        if (tile == (int64_t)t.tiles - 1 && lane < 4) {
+        if ((tile + 1) * (int64_t)tile_elems >= t.n && lane < 4) {          // the last tile
             const int64_t w = (e0 >> 5) * BITS + (int64_t)geo.lanes_used * BITS + lane;
             if (w < words_total) ((uint32_t*)t.packed)[w] = 0u;
         }
@@ -558,7 +558,7 @@ __device__ __forceinline__ void compress_block(const TensorArgs& t, const Geomet
     const int lane = threadIdx.x & 63;
     uint32_t* lds = lds_all + wave * geo.lds_wave_dwords;
     const int64_t tile = block_in_tensor * kWavesPerBlk + wave;
-    if (tile >= (int64_t)t.tiles) return;
+    if (tile * (int64_t)(geo.lanes_used * kPerLane) >= t.n) return;
     // a tile is "full" when all its elements exist and G is a power of two
     const bool full = geo.pow2 && (tile + 1) * (int64_t)(geo.lanes_used * kPerLane) <= t.n;
 #define GACT_C_FULL(DT, BITS) compress_tile<DT, BITS, false, SUM>(t, geo, tile, lds, lane, tile_sum);

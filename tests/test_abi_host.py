@@ -95,6 +95,10 @@ def test_argument_errors_are_reported_before_any_launch():
     assert lib.gact_compress_multi(addr, 0, 32, None, 0, None) == gact.GACT_OK
     assert lib.gact_compress_multi(addr, 2, 32, None, 0, None) == gact.GACT_E_ARG       # no workspace
     assert lib.gact_compress_multi(addr, 2, 32, p16, 8, None) == gact.GACT_E_ARG        # too small
+    for bad in (4, -8, 8 << 48):                         # shard offsets: multiples of 8 in [0, 2^51)
+        d[1].index_base = bad
+        assert lib.gact_compress_multi(addr, 2, 32, p16, 4096, None) == gact.GACT_E_ARG, bad
+    d[1].index_base = 0
     d[1].bits = 5
     assert lib.gact_decompress_multi(addr, 2, 32, p16, 4096, None) == gact.GACT_E_BITS
     d[1].bits = 2; d[0].n = 0; d[1].n = 0

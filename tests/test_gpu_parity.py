@@ -446,3 +446,45 @@ def test_calls_on_two_streams_do_not_interfere(gact):
             p_ref, mn_ref, sc_ref = oracle.compress(x_np[l], G, bits[l], k + 10 * l)
             assert np.array_equal(to_host(bufs[l][0]), p_ref), (k, l)
             assert np.array_equal(to_host(ys[l]), oracle.decompress(p_ref, mn_ref, sc_ref, x_np[l].size, G, bits[l])), (k, l)
+
+
+# ---------------------------------------------------------------------- shards
+@pytest.mark.parametrize("dtype,G,bits", [("f32", 256, 2), ("bf16", 128, 4), ("f32", 96, 8), ("bf16", 1024, 1)])
+def test_shards_with_an_index_base_concatenate_to_the_whole(gact, dtype, G, bits):
+    """A tensor cut at multiples of the group size and compressed shard by shard,
+    each with the tensor's seed and its own offset in the noise stream, gives
+    the bytes of the whole tensor: what one GPU of a sharded tensor would do.
+    Each shard also equals the oracle's result for that slice."""
+    n, seed = 50 * G * 37 + 77, 2**40 + 9
+    x = syn.draw_numpy(syn.NORMAL, n, 61)
+    if dtype == "bf16":
+        x = syn.f32_to_bf16_bits(x)
+    cuts = [0, 7 * G, 7 * G + 32 * G, 900 * G, n]                       # four shards, the last one ragged
+    assert bits * G % 128 == 0 or all((c * bits) % 128 == 0 for c in cuts[:-1])   # shard strings end on 16-byte units
+    xd = to_device(x)
+    whole = gact.gact_compress(xd, G, bits, seed)
+    xs, bufs, ns, bases = [], [], [], []
+    for a, b in zip(cuts[:-1], cuts[1:]):
+        xs.append(xd[a:b].clone())                                      # own 16-byte aligned buffer
+        bufs.append(gact.alloc_compressed(b - a, G, bits, "cuda"))
+        ns.append(b - a); bases.append(a)
+    L = len(ns)
+    descs = gact.make_descs(xs, [b[0] for b in bufs], [b[1] for b in bufs], [b[2] for b in bufs],
+                            [None] * L, ns, [bits] * L, [seed] * L, [xd.dtype] * L, index_bases=bases)
+    ws = torch.empty(gact.gact_multi_workspace_bytes(L), dtype=torch.uint8, device="cuda")
+    gact.gact_compress_multi(descs, L, G, ws)
+    torch.cuda.synchronize()
+    for k, (a, b) in enumerate(zip(cuts[:-1], cuts[1:])):
+        p_ref, mn_ref, sc_ref = oracle.compress_slice(x[a:b], G, bits, seed, a)
+        assert np.array_equal(to_host(bufs[k][0]), p_ref), k
+        assert np.array_equal(to_host(bufs[k][1]).view(np.uint32), mn_ref.view(np.uint32)), k
+        assert np.array_equal(to_host(bufs[k][2]).view(np.uint32), sc_ref.view(np.uint32)), k
+    pb = [gact.gact_packed_bytes(m, bits) for m in ns]
+    exact = [m * bits // 8 for m in ns]                                  # bytes before the 16-byte padding
+    cat = torch.cat([bufs[k][0][:exact[k]] for k in range(L - 1)] + [bufs[L - 1][0]])
+    assert torch.equal(cat, whole[0])
+    assert torch.equal(torch.cat([b[1] for b in bufs]), whole[1])
+    assert torch.equal(torch.cat([b[2] for b in bufs]), whole[2])
+    # a shard compressed without its offset draws other noise
+    other = gact.gact_compress(xs[1], G, bits, seed)
+    assert not torch.equal(other[0], bufs[1][0])
