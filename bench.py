@@ -424,9 +424,9 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
     steps, warmup = max(args.steps // 4, 3), 2
     params = list(model.parameters())
     res = {"no_hooks": run(None, steps, warmup)}
-    res["compress_4bit"] = run(Controller(params, group_size=256, bits=4, seed=0), steps, warmup)
-    res["compress_2bit"] = run(Controller(params, group_size=256, bits=2, seed=0), steps, warmup)
-    res["compress_4bit_swap"] = run(Controller(params, group_size=256, bits=4, seed=0, swap=True), steps, warmup)
+    res["compress_4bit"] = run(Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14), steps, warmup)
+    res["compress_2bit"] = run(Controller(params, group_size=256, bits=2, seed=0, min_numel=1 << 14), steps, warmup)
+    res["compress_4bit_swap"] = run(Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14, swap=True), steps, warmup)
     ref = res["no_hooks"]
     for k, r in res.items():
         r["activation_memory_ratio"] = round(ref["peak_activation_MB"] / max(r["peak_activation_MB"], 1e-9), 2)
