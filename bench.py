@@ -272,6 +272,8 @@ def main() -> int:
         out["cpu_baseline"] = {
             "value": round(2.0 * sample_bytes / (t2 - t0) / 1e9, 3), "unit": "GB/s",
             "cores": all_threads, "kind": "oracle",
+            "compress_GBps": round(sample_bytes / (t1 - t0) / 1e9, 3),
+            "decompress_GBps": round(sample_bytes / (t2 - t1) / 1e9, 3),
             "sample": "first %d tensors of the set (%d elements, %.2f GB), compress %.2f s + decompress %.2f s"
                       % (len(take), acc, sample_bytes / 1e9, t1 - t0, t2 - t1),
             "value_1_thread": round(2.0 * h1.nbytes / (t4 - t3) / 1e9, 3),
