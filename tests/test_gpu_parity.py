@@ -488,3 +488,19 @@ def test_shards_with_an_index_base_concatenate_to_the_whole(gact, dtype, G, bits
     # a shard compressed without its offset draws other noise
     other = gact.gact_compress(xs[1], G, bits, seed)
     assert not torch.equal(other[0], bufs[1][0])
+
+
+def test_index_base_beyond_32_bit_block_numbers(gact):
+    """Offsets whose Philox block number needs more than 32 bits reach the
+    counter's high word; checked against the oracle's slice at the same offset."""
+    G, bits, seed, n = 128, 4, 77, 5000
+    x = syn.draw_numpy(syn.RELU, n, 62)
+    xd = to_device(x)
+    for base in (2**35, 2**43 + 2**35 + 128 * 3, (2**48 - 1) * 8 // 128 * 128):
+        p, mn, sc = gact.alloc_compressed(n, G, bits, "cuda")
+        descs = gact.make_descs([xd], [p], [mn], [sc], [None], [n], [bits], [seed], [xd.dtype], index_bases=[base])
+        ws = torch.empty(gact.gact_multi_workspace_bytes(1), dtype=torch.uint8, device="cuda")
+        gact.gact_compress_multi(descs, 1, G, ws)
+        p_ref, mn_ref, sc_ref = oracle.compress_slice(x, G, bits, seed, base)
+        assert np.array_equal(to_host(p), p_ref), base
+        assert np.array_equal(to_host(mn).view(np.uint32), mn_ref.view(np.uint32)), base
