@@ -59,7 +59,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="resnet50_b64",
-                    choices=sorted(WORKLOADS) + ["grad_sensitivity", "single_1m", "hooks_transformer"])
+                    choices=sorted(WORKLOADS) + ["grad_sensitivity", "single_1m", "hooks_transformer", "fused_footprint"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-elems", type=int, default=800_000_000)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -99,6 +99,8 @@ def main() -> int:
         return bench_single_1m(args, gact, torch, np, dev)
     if args.workload == "hooks_transformer":
         return bench_hooks_transformer(args, gact, torch, np, dev)
+    if args.workload == "fused_footprint":
+        return bench_fused_footprint(args, gact, torch, np, dev)
 
     builder, G, avg_bits, sens_seed, desc = WORKLOADS[args.workload]
     specs = getattr(syn, builder)()
@@ -443,6 +445,51 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
                    "description": "pre-LN encoder with explicit softmax attention, SGD, MSE loss on random data; "
                                   "peak memory above what is allocated before the step"},
         "levels": res,
+    }))
+    return 0
+
+
+def bench_fused_footprint(args, gact, torch, np, dev) -> int:
+    """The compressor with the duplicate footprint (Sec. 5.2) taken in its statistics pass, against
+    the plain compressor and against compressor + separate footprint pass: one tensor of 2^29 fp32
+    elements, G=256, 2 bits, 8 sampled points."""
+    n, G, b, ns = 1 << 29, 256, 2, 8
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(3)
+    x = torch.randn(n, device=dev, generator=gen).relu_()
+    p, mn, sc = gact.alloc_compressed(n, G, b, dev)
+    fp = torch.empty(1 + ns, dtype=torch.float64, device=dev)
+    ws = torch.empty(gact.gact_compress_footprint_workspace_bytes(n, G), dtype=torch.uint8, device=dev)
+    ws2 = torch.empty(gact.gact_reduce_workspace_bytes(1, n), dtype=torch.uint8, device=dev)
+    calls = {"compress": lambda: gact.gact_compress(x, G, b, 1, p, mn, sc),
+             "footprint": lambda: gact.gact_footprint(x, ns, fp, ws2),
+             "compress_footprint": lambda: gact.gact_compress_footprint(x, G, b, 1, ns, p, mn, sc, fp, ws)}
+    ms = {}
+    t0 = time.perf_counter()
+    for name, f in calls.items():
+        for _ in range(args.warmup):
+            f()
+        torch.cuda.synchronize()
+        t = []
+        for _ in range(args.steps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); f(); e1.record(); e1.synchronize()
+            t.append(e0.elapsed_time(e1))
+        ms[name] = float(np.median(t))
+    wall = time.perf_counter() - t0
+    alg = n * 4 + n * b // 8 + (n // G) * 8 + (n // 2048) * 8          # + one partial sum per tile
+    print(json.dumps({
+        "metric": "compress with fused footprint, algorithmic GB/s, 1xMI355X",
+        "value": round(alg / ms["compress_footprint"] / 1e6, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(wall * 1e3 / (3 * args.steps), 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "fused_footprint", "elements": n, "group_size": G, "bits": b, "n_samples": ns},
+        "ms": {k: round(v, 4) for k, v in ms.items()},
+        "separate_passes_ms": round(ms["compress"] + ms["footprint"], 4),
+        "roofline": {"bound": "hbm", "kernel": "gact::compress_sum_kernel",
+                     "achieved": round(alg / ms["compress_footprint"] / 1e6, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(alg / ms["compress_footprint"] / 1e6 / HBM_PEAK_GBPS, 4),
+                     "traffic": None},
     }))
     return 0
 

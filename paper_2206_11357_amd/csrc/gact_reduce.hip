@@ -244,25 +244,27 @@ __global__ __launch_bounds__(kRedThreads) void grad_stats_kernel(const ReduceArg
 }
 
 // ------------------------------------------------------------ final addition
-// out[j] = scale * sum_i partial[j * count + i], one block of 1024 threads per
-// output.  Thread t adds the partials t, t + 1024, ... eight at a time (eight
-// independent loads in flight), then the block adds the thread sums in a tree:
-// the order is fixed, so the result is reproducible.
+// out[j] = scale * sum_i partial[j * count + i] in a fixed order, so that the
+// result is reproducible.  One block of 1024 threads per output: thread t adds
+// the terms t, t + 1024, ... eight at a time (eight independent loads in
+// flight), then the block adds the thread sums in a tree.  `stride` is the
+// distance between terms (1, or the chunk length after fold_kernel).
 constexpr int kFinThreads = 1024;
 __global__ __launch_bounds__(kFinThreads) void finish_kernel(const double* __restrict__ partial,
-                                                             uint32_t count, double scale,
+                                                             uint32_t count, uint32_t stride,
+                                                             size_t out_pitch, double scale,
                                                              double* __restrict__ out) {
     __shared__ double lds[kFinThreads / 64];
-    const double* p = partial + (size_t)blockIdx.x * count;
+    const double* p = partial + (size_t)blockIdx.x * out_pitch;
     double acc = 0.0;
     uint32_t i = threadIdx.x;
     for (; i + 7u * kFinThreads < count; i += 8u * kFinThreads) {
         double v[8];
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = p[i + (uint32_t)k * kFinThreads];
+        for (int k = 0; k < 8; ++k) v[k] = p[(size_t)(i + (uint32_t)k * kFinThreads) * stride];
         acc += ((v[0] + v[1]) + (v[2] + v[3])) + ((v[4] + v[5]) + (v[6] + v[7]));
     }
-    for (; i < count; i += kFinThreads) acc += p[i];
+    for (; i < count; i += kFinThreads) acc += p[(size_t)i * stride];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
     if ((threadIdx.x & 63) == 0) lds[threadIdx.x >> 6] = acc;
@@ -274,6 +276,36 @@ __global__ __launch_bounds__(kFinThreads) void finish_kernel(const double* __res
     }
 }
 
+// First level for long lists: block (k, j) adds the terms [k * chunk, (k + 1) * chunk)
+// of output j and leaves the sum in the first of them (it only touches its own chunk).
+__global__ __launch_bounds__(kRedThreads) void fold_kernel(double* __restrict__ partial, uint32_t count,
+                                                           uint32_t chunk) {
+    __shared__ double lds[4];
+    double* p = partial + (size_t)blockIdx.y * count + (size_t)blockIdx.x * chunk;
+    const uint32_t left = count - blockIdx.x * chunk;
+    const uint32_t m = left < chunk ? left : chunk;
+    double acc = 0.0;
+    for (uint32_t i = threadIdx.x; i < m; i += kRedThreads) acc += p[i];
+    const double s = block_sum(acc, lds);
+    if (threadIdx.x == 0) p[0] = s;
+}
+
+// Enqueues the final addition of `count` terms for each of `nout` outputs.
+static void launch_finish(double* d_partial, unsigned count, int nout, double scale, double* d_out,
+                          hipStream_t s) {
+    constexpr unsigned kFoldBlocks = 128;
+    if (count <= 32768u) {
+        hipLaunchKernelGGL(finish_kernel, dim3(nout), dim3(kFinThreads), 0, s, d_partial, count, 1u,
+                           (size_t)count, scale, d_out);
+        return;
+    }
+    const unsigned chunk = (count + kFoldBlocks - 1) / kFoldBlocks;
+    const unsigned folded = (count + chunk - 1) / chunk;
+    hipLaunchKernelGGL(fold_kernel, dim3(folded, nout), dim3(kRedThreads), 0, s, d_partial, count, chunk);
+    hipLaunchKernelGGL(finish_kernel, dim3(nout), dim3(kFinThreads), 0, s, d_partial, folded, chunk,
+                       (size_t)count, scale, d_out);
+}
+
 }  // namespace gact
 
 extern "C" int gact_launch_diff_sq(const gact::ReduceArgs* d_table, const uint32_t* d_first, int K,
@@ -282,8 +314,7 @@ extern "C" int gact_launch_diff_sq(const gact::ReduceArgs* d_table, const uint32
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(gact::diff_sq_kernel, dim3(blocks), dim3(gact::kRedThreads), 0, s, d_table, d_first,
                        K, d_partial);
-    hipLaunchKernelGGL(gact::finish_kernel, dim3(1), dim3(gact::kFinThreads), 0, s, d_partial, blocks,
-                       scale, d_out);
+    gact::launch_finish(d_partial, blocks, 1, scale, d_out, s);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -293,15 +324,14 @@ extern "C" int gact_launch_grad_stats(const gact::ReduceArgs* d_table, const uin
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(gact::grad_stats_kernel, dim3(blocks), dim3(gact::kRedThreads), 0, s, d_table,
                        d_first, K, rt, blocks, d_partial);
-    hipLaunchKernelGGL(gact::finish_kernel, dim3(2), dim3(gact::kFinThreads), 0, s, d_partial, blocks,
-                       1.0, d_out);
+    gact::launch_finish(d_partial, blocks, 2, 1.0, d_out, s);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 // out[0 .. nout) = 0 through a kernel (no memset node, so callers may capture it)
 extern "C" int gact_launch_zero(double* d_out, int nout, void* stream) {
     hipLaunchKernelGGL(gact::finish_kernel, dim3(nout), dim3(gact::kFinThreads), 0, (hipStream_t)stream,
-                       (const double*)d_out, 0u, 0.0, d_out);
+                       (const double*)d_out, 0u, 1u, (size_t)0, 0.0, d_out);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
@@ -309,8 +339,7 @@ extern "C" int gact_launch_zero(double* d_out, int nout, void* stream) {
 extern "C" int gact_launch_footprint_finish(const gact::ReduceArgs* r, unsigned count, double* d_partial,
                                             int n_samples, double* d_out, void* stream) {
     hipStream_t s = (hipStream_t)stream;
-    hipLaunchKernelGGL(gact::finish_kernel, dim3(1), dim3(gact::kFinThreads), 0, s, d_partial, count,
-                       1.0, d_out);
+    gact::launch_finish(d_partial, count, 1, 1.0, d_out, s);
     if (n_samples > 0)
         hipLaunchKernelGGL(gact::sample_kernel, dim3((n_samples + 255) / 256), dim3(256), 0, s, *r,
                            n_samples, d_out);
@@ -321,8 +350,7 @@ extern "C" int gact_launch_footprint(const gact::ReduceArgs* r, unsigned blocks,
                                      int n_samples, double* d_out, void* stream) {
     hipStream_t s = (hipStream_t)stream;
     hipLaunchKernelGGL(gact::sum_kernel, dim3(blocks), dim3(gact::kRedThreads), 0, s, *r, d_partial);
-    hipLaunchKernelGGL(gact::finish_kernel, dim3(1), dim3(gact::kFinThreads), 0, s, d_partial, blocks,
-                       1.0, d_out);
+    gact::launch_finish(d_partial, blocks, 1, 1.0, d_out, s);
     if (n_samples > 0)
         hipLaunchKernelGGL(gact::sample_kernel, dim3((n_samples + 255) / 256), dim3(256), 0, s, *r,
                            n_samples, d_out);
