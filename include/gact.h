@@ -4,7 +4,7 @@
  *
  * What the calls compute
  *   The paper's compressor Q is a per-group stochastic-rounding quantizer
- *   (Sec. 5: "per-group quantizer"; App. A.4: transform
+ *   (Sec. 5: quantisation per group; App. A.4: transform
  *   T(h_j) = (2^b-1)(h_j - min h)/(max h - min h), round up with probability
  *   T - floor(T), otherwise down, and map back with the inverse of T).  A
  *   context tensor is a flattened vector (Sec. 3.1); it is cut into groups of
@@ -25,7 +25,8 @@
  *   Philox4x32-10 (Salmon et al., SC'11), key = (low, high 32 bits of seed),
  *   counter = (low, high 32 bits of i/8, 0, 0).  The four output words hold
  *   eight 16-bit slots, low half first; element i takes slot i%8 and
- *   u = (slot + 0.5) / 65536.  The stream is a function of (seed, i) only, so
+ *   u = (slot + 0.5) / 65536.  (For a shard, i counts from the descriptor's
+ *   index_base.)  The stream is a function of (seed, i) only, so
  *   results never depend on launch shape or on single- vs multi-tensor calls,
  *   and the same seed replays the same compression (Alg. 1 of the paper relies
  *   on replayable per-tensor seeds).
@@ -192,9 +193,9 @@ int gact_sensitivity(const gact_grad_pair *h_pairs, int K, int bits, double *d_o
                      void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
- * Running gradient statistics for the a-posteriori alert of Sec. 4.2 ("the
- * overall gradient variance can be computed by maintaining a running mean of
- * the gradient").  Step t >= 1 over K parameter buffers, binary32 per element:
+ * Running gradient statistics for the a-posteriori alert of Sec. 4.2, which
+ * needs the variance of the gradient and obtains it from a running mean kept
+ * over the iterations.  Step t >= 1 over K parameter buffers, binary32 per element:
  *     mean <- mean + (g - mean) * rt,    rt = (float)(1 / t),
  * and, in binary64, d_out[0] = sum g^2, d_out[1] = sum mean_new^2.  With the
  * caller's running average s_t of d_out[0], Var[g] ~ s_t - d_out[1].
