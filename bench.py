@@ -71,6 +71,9 @@ def main() -> int:
               "single-GPU boxes; run with --gpus 1", file=sys.stderr)
         return 2
 
+    # The probe is a program of its own: it runs, and ends, before this process touches the GPU.
+    ceilings = traffic_ceilings() if args.workload in WORKLOADS and not args.copy_calibration else None
+
     import numpy as np
     import torch
     import paper_2206_11357_amd as gact
@@ -236,6 +239,7 @@ def main() -> int:
         "per_tensor_calls": {"calls_per_direction": L, "compress_ms": round(pt_c, 4), "decompress_ms": round(pt_d, 4),
                              "fused_pct_hbm_peak": round(100 * 2 * alg_bytes / (pt_c + pt_d) / 1e6 / HBM_PEAK_GBPS, 2)},
         "copy_ceiling": copy_ceiling(torch, np, dev),
+        "traffic_ceilings": ceilings,
         "hbm_peak": hbm_peak_info(torch),
     }
 
@@ -300,6 +304,28 @@ def copy_ceiling(torch, np, dev) -> dict:
     m = float(np.median(ms))
     return {"kernel": "torch copy_ of 1 GiB", "GBps_read_plus_write": round(2 * src.numel() * 4 / m / 1e6, 1),
             "pct_hbm_peak": round(100 * 2 * src.numel() * 4 / m / 1e6 / HBM_PEAK_GBPS, 2)}
+
+
+def traffic_ceilings():
+    """What kernels without arithmetic reach on this machine for the codec's traffic mixes (same access
+    shape: 8 KB per wavefront in coalesced 16-byte non-temporal accesses, 512 B the other way):
+    the memory system's own limit next to which `roofline.achieved` should be read.  None when the
+    probe has not been built."""
+    import subprocess
+    exe = os.path.join(ROOT, "paper_2206_11357_amd", "traffic_probe.bin")
+    if not os.path.exists(exe):
+        return None
+    try:
+        r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+        if r.returncode != 0:
+            return {"error": r.stderr.strip()[-200:]}
+        out = json.loads(r.stdout.strip().splitlines()[-1])
+        for k in list(out):
+            if k.endswith("_GBps"):
+                out[k.replace("_GBps", "_pct_hbm_peak")] = round(100 * out[k] / HBM_PEAK_GBPS, 1)
+        return out
+    except Exception as e:                                   # measurement aid only
+        return {"error": str(e)[-200:]}
 
 
 def hbm_peak_info(torch) -> dict:

@@ -11,6 +11,9 @@ LIB = os.path.join(HERE, "libgact.so")
 SOURCES = [os.path.join(CSRC, "gact_kernels.hip"), os.path.join(CSRC, "gact_reduce.hip"),
            os.path.join(CSRC, "gact_api.cpp")]
 
+PROBE = os.path.join(HERE, "traffic_probe.bin")     # standalone measurement tool, not part of the library
+PROBE_SOURCE = os.path.join(CSRC, "traffic_probe.hip")
+
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950",
@@ -30,7 +33,20 @@ def build(verbose: bool = False) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     os.replace(tmp, LIB)
+    build_probe(verbose)
     return LIB
+
+
+def build_probe(verbose: bool = False) -> str:
+    """The HBM traffic-ceiling probe bench.py runs beside the workload."""
+    tmp = PROBE + ".tmp%d" % os.getpid()
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument", "-x", "hip", PROBE_SOURCE, "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, PROBE)
+    return PROBE
 
 
 if __name__ == "__main__":
