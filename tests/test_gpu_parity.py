@@ -504,3 +504,17 @@ def test_index_base_beyond_32_bit_block_numbers(gact):
         p_ref, mn_ref, sc_ref = oracle.compress_slice(x, G, bits, seed, base)
         assert np.array_equal(to_host(p), p_ref), base
         assert np.array_equal(to_host(mn).view(np.uint32), mn_ref.view(np.uint32)), base
+
+
+def test_multi_tensor_three_thousand_tiny_tensors(gact):
+    """A long table (uploaded to the workspace, 12 search steps per block) of
+    tensors that are mostly smaller than one tile."""
+    rng = np.random.default_rng(5)
+    specs = []
+    for k in range(3000):
+        n = int(rng.integers(1, 700))
+        x = syn.draw_numpy(syn.NORMAL, n, 9000 + k)
+        if k % 2:
+            x = syn.f32_to_bf16_bits(x)
+        specs.append((x, int(rng.choice([1, 2, 4, 8])), k))
+    multi_case(gact, specs, 64)
