@@ -48,6 +48,8 @@ WORKLOADS = {
                        "96 saved tensors of a BERT-large-shaped encoder, batch 32 x seq 512, bf16, G=256, allocator avg 4 bits"),
     "gcn_arxiv": ("gcn_set", 256, 2.0, 4999,
                   "3 GCN activations 169343 x 256, fp32, G=256, 2 bits"),
+    "gcn_arxiv_b4": ("gcn_set", 256, 4.0, 4999,
+                     "3 GCN activations 169343 x 256, fp32, G=256, 4 bits"),
     "vit_large_b128": ("vit_large_set", 128, 3.0, 5999,
                        "400 saved tensors of a ViT-L/16-shaped model, batch 128, bf16, G=128, allocator avg 3 bits"),
 }
@@ -110,8 +112,8 @@ def main() -> int:
     L = len(specs)
     numel = np.array([s.numel for s in specs], dtype=np.int64)
     sens = syn.lognormal_sensitivities(L, sens_seed)
-    if args.workload == "gcn_arxiv":
-        sens[:] = 1.0                       # fixed 2 bits everywhere
+    if args.workload.startswith("gcn_arxiv"):
+        sens[:] = 1.0                       # the same width everywhere
     torch_dt = {"f32": torch.float32, "bf16": torch.bfloat16}
     esize = {"f32": 4, "bf16": 2}
 
