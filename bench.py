@@ -46,6 +46,8 @@ WORKLOADS = {
                      "53 conv outputs of a ResNet-50-shaped net, batch 64, fp32, G=256, allocator avg 2 bits"),
     "bert_large_b32": ("bert_large_set", 256, 4.0, 3999,
                        "96 saved tensors of a BERT-large-shaped encoder, batch 32 x seq 512, bf16, G=256, allocator avg 4 bits"),
+    "bert_large_b32_uniform4": ("bert_large_set", 256, 4.0, 3999,
+                                "96 saved tensors of a BERT-large-shaped encoder, batch 32 x seq 512, bf16, G=256, 4 bits everywhere"),
     "gcn_arxiv": ("gcn_set", 256, 2.0, 4999,
                   "3 GCN activations 169343 x 256, fp32, G=256, 2 bits"),
     "gcn_arxiv_b4": ("gcn_set", 256, 4.0, 4999,
@@ -112,7 +114,7 @@ def main() -> int:
     L = len(specs)
     numel = np.array([s.numel for s in specs], dtype=np.int64)
     sens = syn.lognormal_sensitivities(L, sens_seed)
-    if args.workload.startswith("gcn_arxiv"):
+    if args.workload.startswith("gcn_arxiv") or args.workload.endswith("_uniform4"):
         sens[:] = 1.0                       # the same width everywhere
     torch_dt = {"f32": torch.float32, "bf16": torch.bfloat16}
     esize = {"f32": 4, "bf16": 2}
