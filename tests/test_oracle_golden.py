@@ -6,8 +6,6 @@ field that the oracle's arithmetic or noise stream changed."""
 import os
 import sys
 
-import numpy as np
-import pytest
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, os.path.join(HERE, "golden"))

@@ -7,7 +7,6 @@ Python's unbounded integers (no shared code, different word handling), and
 against what a uniform, independent stream must satisfy.
 """
 import numpy as np
-import pytest
 
 import oracle
 

@@ -106,7 +106,6 @@ def test_algorithm_1_on_a_linear_gradient_recovers_the_compression_variance():
     """g(Q(h)) = w * Q(h) (elementwise).  Two runs that differ only in the
     compressor's seed give E[1/2 ||g0 - g1||^2] = sum_j w_j^2 Var[Q(h)_j], and
     Var[Q(h)_j] = frac_j (1 - frac_j) step^2 <= 1/4 step^2 (Sec. 4.1)."""
-    from fractions import Fraction
     rng = np.random.default_rng(3)
     n, G, bits, pairs = 1024, 256, 2, 400
     h = syn.draw_numpy(syn.NORMAL, n, 5)
