@@ -11,11 +11,9 @@ LIB = os.path.join(HERE, "libgact.so")
 SOURCES = [os.path.join(CSRC, "gact_kernels.hip"), os.path.join(CSRC, "gact_reduce.hip"),
            os.path.join(CSRC, "gact_api.cpp")]
 
-# standalone measurement tools, not part of the library
+# standalone measurement tool, not part of the library
 PROBE = os.path.join(HERE, "traffic_probe.bin")
 PROBE_SOURCE = os.path.join(CSRC, "traffic_probe.hip")
-RATE_PROBE = os.path.join(HERE, "valu_rate_probe.bin")
-RATE_PROBE_SOURCE = os.path.join(CSRC, "valu_rate_probe.hip")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -41,15 +39,14 @@ def build(verbose: bool = False) -> str:
 
 
 def build_probe(verbose: bool = False) -> str:
-    """The HBM traffic-ceiling probe bench.py runs beside the workload, and the VALU issue-rate probe."""
-    for source, exe in ((PROBE_SOURCE, PROBE), (RATE_PROBE_SOURCE, RATE_PROBE)):
-        tmp = exe + ".tmp%d" % os.getpid()
-        cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
-               "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument", "-x", "hip", source, "-o", tmp]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        subprocess.check_call(cmd)
-        os.replace(tmp, exe)
+    """The HBM traffic-ceiling probe bench.py runs beside the workload."""
+    tmp = PROBE + ".tmp%d" % os.getpid()
+    cmd = [HIPCC, "-O3", "-std=c++17", "--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang",
+           "-packed-fp32-ops", "-Wall", "-Wno-unused-command-line-argument", "-x", "hip", PROBE_SOURCE, "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, PROBE)
     return PROBE
 
 

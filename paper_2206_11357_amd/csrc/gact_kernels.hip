@@ -114,25 +114,119 @@ __device__ __forceinline__ void group_minmax_any(float& mn, float& mx, int lpg, 
 }
 
 // ------------------------------------------------------------------- Philox
-// Philox4x32-10 (Salmon et al., SC'11) on counter (c0, c1, 0, 0).
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0,
-                                              uint32_t k1, uint32_t w[4]) {
-    uint32_t c2 = 0u, c3 = 0u;
+// Philox4x32-10 (Salmon et al., SC'11) on counter (c0, c1, 0, 0), key (k0, k1).
+constexpr uint32_t kPhiloxM0 = 0xD2511F53u, kPhiloxM1 = 0xCD9E8D57u;
+constexpr uint32_t kPhiloxW0 = 0x9E3779B9u, kPhiloxW1 = 0xBB67AE85u;
+
+// three-input xor in one v_bitop3_b32 (truth table 0x96)
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
+// rounds FIRST .. 9 (round r uses the key bumped r times)
+template <int FIRST>
+__device__ __forceinline__ void philox_rounds(uint32_t& c0, uint32_t& c1, uint32_t& c2, uint32_t& c3,
+                                              uint32_t k0, uint32_t k1) {
 #pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
-        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        // three-input xor in one v_bitop3_b32 (truth table 0x96)
-        const uint32_t n0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
-        const uint32_t n2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
+    for (int r = FIRST; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
+        const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
+        const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0 + (uint32_t)r * kPhiloxW0);
+        const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1 + (uint32_t)r * kPhiloxW1);
         c1 = (uint32_t)p1;
         c3 = (uint32_t)p0;
         c0 = n0;
         c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
     }
-    w[0] = c0; w[1] = c1; w[2] = c2; w[3] = c3;
+}
+
+// Rounds 0..2 of a block whose counter is (c0, c1u, 0, 0) with the high word c1u
+// and the key uniform over the wavefront -- the case for every block of a tile
+// unless the low counter word wraps inside the tile.  Counter words 2 and 3
+// being zero, part of these rounds is the same for every lane and is computed
+// once per wavefront, on the scalar unit (PhiloxUniform):
+//   round 0: M1 * 0 = 0, so word 0 becomes c1u ^ k0 (uniform) and word 1 is 0;
+//   round 1: M0 * (uniform word 0) is a scalar product; its low half is the
+//            new, uniform, word 3;
+//   round 2: the uniform word 3 and the key fold into one scalar operand.
+// Four 32 x 32 -> 64 multiplies per block instead of six.
+struct PhiloxUniform {
+    uint32_t f2, g2;
+    __device__ __forceinline__ PhiloxUniform(uint32_t c1u, uint32_t k0, uint32_t k1) {
+        const uint32_t a0 = c1u ^ k0;                                      // round 0, word 0
+        const uint64_t P0 = (uint64_t)kPhiloxM0 * a0;                       // round 1 product
+        f2 = (uint32_t)(P0 >> 32) ^ (k1 + kPhiloxW1);                       // round 1: word 2 = f2 ^ old word 3
+        g2 = (uint32_t)P0 ^ (k1 + 2u * kPhiloxW1);                          // round 2: word 2 = hi(M0 word 0) ^ g2
+    }
+};
+__device__ __forceinline__ void philox_head_uniform(uint32_t c0, const PhiloxUniform& u, uint32_t k0,
+                                                    uint32_t k1, uint32_t st[4]) {
+    const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;                           // round 0
+    const uint32_t a2 = (uint32_t)(p0 >> 32) ^ k1;
+    const uint32_t a3 = (uint32_t)p0;
+    const uint64_t p1 = (uint64_t)kPhiloxM1 * a2;                           // round 1
+    const uint32_t b0 = (uint32_t)(p1 >> 32) ^ (k0 + kPhiloxW0);
+    const uint32_t b1 = (uint32_t)p1;
+    const uint32_t b2 = a3 ^ u.f2;
+    const uint64_t q0 = (uint64_t)kPhiloxM0 * b0;                           // round 2
+    const uint64_t q1 = (uint64_t)kPhiloxM1 * b2;
+    st[0] = xor3((uint32_t)(q1 >> 32), b1, k0 + 2u * kPhiloxW0);
+    st[1] = (uint32_t)q1;
+    st[2] = (uint32_t)(q0 >> 32) ^ u.g2;
+    st[3] = (uint32_t)q0;
+}
+
+// The same three rounds for any per-lane 64-bit block number.
+__device__ __forceinline__ void philox_head_any(uint64_t blk, uint32_t k0, uint32_t k1, uint32_t st[4]) {
+    uint32_t c0 = (uint32_t)blk, c1 = (uint32_t)(blk >> 32), c2 = 0u, c3 = 0u;
+#pragma unroll
+    for (int r = 0; r < 3; ++r) {
+        const uint64_t p0 = (uint64_t)kPhiloxM0 * c0;
+        const uint64_t p1 = (uint64_t)kPhiloxM1 * c2;
+        const uint32_t n0 = xor3((uint32_t)(p1 >> 32), c1, k0 + (uint32_t)r * kPhiloxW0);
+        const uint32_t n2 = xor3((uint32_t)(p0 >> 32), c3, k1 + (uint32_t)r * kPhiloxW1);
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+    }
+    st[0] = c0; st[1] = c1; st[2] = c2; st[3] = c3;
+}
+
+// Three-input min / max of finite values.  As assembly because the compiler
+// puts a canonicalising v_max_f32 x, x in front of values it cannot prove to be
+// free of signalling NaNs (everything that was widened from bf16 with bit
+// operations); non-finite input is outside the contract.
+__device__ __forceinline__ float fmin3(float a, float b, float c) {
+    float r;
+    asm("v_min3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+__device__ __forceinline__ float fmax3(float a, float b, float c) {
+    float r;
+    asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// x[j] <- x[j] + b for eight values, rounded toward minus infinity.  The
+// wavefront's binary32 rounding mode (MODE bits 1:0) is switched to round-down
+// for exactly these eight additions and back to nearest-even; the block is one
+// volatile statement, so no other floating-point instruction can be scheduled
+// into it and everything outside keeps the nearest-even contract.
+__device__ __forceinline__ void add8_round_down(float (&x)[8], float b) {
+    asm volatile(
+        "s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 2\n\t"
+        "v_add_f32 %0, %0, %8\n\t"
+        "v_add_f32 %1, %1, %8\n\t"
+        "v_add_f32 %2, %2, %8\n\t"
+        "v_add_f32 %3, %3, %8\n\t"
+        "v_add_f32 %4, %4, %8\n\t"
+        "v_add_f32 %5, %5, %8\n\t"
+        "v_add_f32 %6, %6, %8\n\t"
+        "v_add_f32 %7, %7, %8\n\t"
+        "s_setreg_imm32_b32 hwreg(HW_REG_MODE, 0, 2), 0"
+        : "+v"(x[0]), "+v"(x[1]), "+v"(x[2]), "+v"(x[3]), "+v"(x[4]), "+v"(x[5]), "+v"(x[6]), "+v"(x[7])
+        : "v"(b));
 }
 
 // Instructions the compiler does not select on its own.
@@ -287,7 +381,7 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
                                               double* __restrict__ tile_sum) {
     constexpr uint32_t B = (1u << BITS) - 1u;
     const int tile_elems = geo.lanes_used * kPerLane;
-    const int64_t e0 = tile * (int64_t)tile_elems;
+    const int64_t e0 = tile * (int64_t)tile_elems;       // `tile` is uniform over the wavefront
     int ne = tile_elems;
     if (EDGE) {
         const int64_t left = t.n - e0;
@@ -318,9 +412,10 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
     // group statistics
     float mn, mx;
     if (!EDGE) {
-        mn = v[0]; mx = v[0];
+        mn = fmin3(v[0], v[1], v[2]); mx = fmax3(v[0], v[1], v[2]);
 #pragma unroll
-        for (int j = 1; j < kPerLane; ++j) { mn = fmin2(mn, v[j]); mx = fmax2(mx, v[j]); }
+        for (int j = 3; j + 1 < kPerLane; j += 2) { mn = fmin3(mn, v[j], v[j + 1]); mx = fmax3(mx, v[j], v[j + 1]); }
+        mn = fmin3(mn, v[kPerLane - 1], v[kPerLane - 1]); mx = fmax3(mx, v[kPerLane - 1], v[kPerLane - 1]);
         group_minmax_pow2(mn, mx, geo.lpg);
     } else {
         mn = __builtin_inff(); mx = -__builtin_inff();
@@ -352,40 +447,61 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
     // C = ceil(T) and c = C mod 2^17:  round up  <=>  2 frac 2^16 > 2r + 1
     // <=>  c >= 2r + 2  <=>  2r + 1 - C < -(floor(t) 2^17), hence
     //     -q = (2r + 1 - C) >> 17   (arithmetic shift).
-    // C comes from one convert-with-floor of -T, 2r + (1 - C) from one 16-bit
-    // multiply-add that also selects the half word.  Codes are accumulated
-    // negated, last element first, one shift-add each; the word is negated at
-    // the end (two's complement: sum of (-q_j) << (j BITS) = -(packed word)).
+    // 1 - C = floor(-T) + 1 comes out of one addition rounded toward minus
+    // infinity: for |T| < 2^22 (codes of up to 4 bits: T <= 15 * 2^17 (1 + 2^-23))
+    // the sum -T + (1.5 * 2^23 + 1) lies in [2^23, 2^24), where binary32 has a
+    // spacing of 1, so its round-down value is 1.5 * 2^23 + 1 + floor(-T) exactly
+    // and its bit pattern is 0x4B400001 + floor(-T).  The 16-bit multiply-add
+    // that selects the noise half word adds 2r to that pattern, and because
+    // 0x4B400000 is a multiple of 2^17 the shift gives kBias - q with
+    // kBias = 0x4B400000 >> 17.  8-bit codes (T up to 2^25) use a
+    // convert-with-floor instead (kBias = 0).  The biased negated codes are
+    // accumulated last element first, one shift-add each, and the word is
+    // kBias * (sum of the field weights) - accumulator, all modulo 2^32.
+    constexpr bool kMagic = BITS <= 4;
+    constexpr uint32_t kBias = kMagic ? (0x4B400000u >> 17) : 0u;
+    constexpr uint32_t kFieldWeights = BITS == 1 ? 0xFFFFFFFFu : BITS == 2 ? 0x55555555u
+                                     : BITS == 4 ? 0x11111111u : 0x01010101u;
+    constexpr uint32_t kBiasWord = kBias * kFieldWeights;          // modulo 2^32
     uint32_t acc[BITS];
 #pragma unroll
     for (int w = 0; w < BITS; ++w) acc[w] = 0u;
     const float ninv17 = -(inv * 0x1p17f);
-    const uint64_t blk0 = t.blk_base() + ((uint64_t)(e0 + my0) >> 3);
+    // block numbers of this lane: tile_blk + 4 lane + (0..3); the high word is the
+    // same for the whole tile unless the low word wraps inside it
+    const uint64_t tile_blk = t.blk_base() + ((uint64_t)e0 >> 3);
+    const bool hi_uniform = (uint32_t)tile_blk <= 0xFFFFFEFFu;
+    const PhiloxUniform pu((uint32_t)(tile_blk >> 32), t.seed_lo, t.seed_hi);
+    const uint32_t lane_c0 = (uint32_t)tile_blk + 4u * (uint32_t)lane;
 #pragma unroll
     for (int c = 3; c >= 0; --c) {
         uint32_t r[4];
-        const uint64_t blk = blk0 + (uint64_t)c;
-        philox4x32_10((uint32_t)blk, (uint32_t)(blk >> 32), t.seed_lo, t.seed_hi, r);
+        if (hi_uniform) philox_head_uniform(lane_c0 + (uint32_t)c, pu, t.seed_lo, t.seed_hi, r);
+        else philox_head_any(tile_blk + (uint64_t)(4 * lane + c), t.seed_lo, t.seed_hi, r);
+        philox_rounds<3>(r[0], r[1], r[2], r[3], t.seed_lo, t.seed_hi);
+        float tn[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tn[j] = (v[c * 8 + j] - mn) * ninv17;   // -T, T in [0, 2^25)
+        if (kMagic) add8_round_down(tn, 12582913.0f);                      // 1.5 * 2^23 + 1
 #pragma unroll
         for (int j = 7; j >= 0; --j) {
             const int e = c * 8 + j;
-            const float d = v[e] - mn;
-            const float tn = d * ninv17;                          // -T, T in [0, 2^25)
-            const uint32_t n1 = (uint32_t)(cvt_floor_i32(tn) + 1);  // 1 - C
+            const uint32_t n1 = kMagic ? __builtin_bit_cast(uint32_t, tn[j])
+                                       : (uint32_t)(cvt_floor_i32(tn[j]) + 1);     // (bias +) 1 - C
             const uint32_t y = (j & 1) ? mad2_hi16(r[j >> 1], n1) : mad2_lo16(r[j >> 1], n1);
-            int32_t nq = (int32_t)y >> 17;                        // -q
+            int32_t nq = (int32_t)y >> 17;                        // kBias - q
             // t <= B (1 + 2^-23): an overshoot's fraction is below the smallest
             // noise value 2^-17 unless B = 255, so only 8-bit codes can round
             // past the top level
             if (BITS == 8) nq = nq > -(int32_t)B ? nq : -(int32_t)B;
-            if (EDGE && my0 + e >= ne) nq = 0;
+            if (EDGE && my0 + e >= ne) nq = (int32_t)kBias;
             const int w = (e * BITS) >> 5;
             acc[w] = (acc[w] << BITS) + (uint32_t)nq;
         }
     }
     uint32_t out[BITS];
 #pragma unroll
-    for (int w = 0; w < BITS; ++w) out[w] = 0u - acc[w];
+    for (int w = 0; w < BITS; ++w) out[w] = kBiasWord - acc[w];
 
     // lane i owns dwords [i*BITS, (i+1)*BITS) of the tile's packed words
     const int64_t word0 = (e0 >> 5) * BITS + (int64_t)lane * BITS;
@@ -557,7 +673,7 @@ __device__ __forceinline__ void compress_block(const TensorArgs& t, const Geomet
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     uint32_t* lds = lds_all + wave * geo.lds_wave_dwords;
-    const int64_t tile = block_in_tensor * kWavesPerBlk + wave;
+    const int64_t tile = block_in_tensor * kWavesPerBlk + __builtin_amdgcn_readfirstlane(wave);
     if (tile * (int64_t)(geo.lanes_used * kPerLane) >= t.n) return;
     // a tile is "full" when all its elements exist and G is a power of two
     const bool full = geo.pow2 && (tile + 1) * (int64_t)(geo.lanes_used * kPerLane) <= t.n;
@@ -590,8 +706,10 @@ __device__ __forceinline__ void run_block(const TensorArgs& t, const Geometry& g
     else decompress_block(t, geo, block_in_tensor);
 }
 
+// Eight resident wavefronts per SIMD (at most 64 VGPRs) for every kernel: the
+// bf16 compressor, which is bound by instruction issue, needs all of them.
 template <bool COMPRESS>
-__global__ __launch_bounds__(kBlockThreads) void single_kernel(TensorArgs t, Geometry geo) {
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void single_kernel(TensorArgs t, Geometry geo) {
     run_block<COMPRESS>(t, geo, (int64_t)blockIdx.x);
 }
 
@@ -614,7 +732,7 @@ __device__ __forceinline__ int find_tensor(const uint32_t* first_block, int L, u
 
 // Table in device memory (the caller's workspace): any number of tensors.
 template <bool COMPRESS>
-__global__ __launch_bounds__(kBlockThreads) void multi_kernel(const TensorArgs* __restrict__ table,
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void multi_kernel(const TensorArgs* __restrict__ table,
                                                               const uint32_t* __restrict__ first_block,
                                                               int L, Geometry geo) {
     const uint32_t b = blockIdx.x;
@@ -626,7 +744,7 @@ __global__ __launch_bounds__(kBlockThreads) void multi_kernel(const TensorArgs* 
 // Table passed by value in the kernel arguments: up to kInlineTensors tensors,
 // no upload and no host synchronisation before the launch.
 template <bool COMPRESS>
-__global__ __launch_bounds__(kBlockThreads) void multi_inline_kernel(InlineTable tab, Geometry geo) {
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void multi_inline_kernel(InlineTable tab, Geometry geo) {
     const uint32_t b = blockIdx.x;
     const int l = find_tensor(tab.first_block, tab.L, b);
     run_block<COMPRESS>(tab.t[l], geo, (int64_t)(b - tab.first_block[l]));
