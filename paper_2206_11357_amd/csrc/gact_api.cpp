@@ -95,6 +95,28 @@ int refuse_if_capturing(void* stream) {
 }
 
 size_t table_bytes(int L) { return ((size_t)L * sizeof(gact::TensorArgs) + 15) / 16 * 16; }
+size_t first_bytes(int L) { return ((size_t)(L + 1) * sizeof(uint32_t) + 15) / 16 * 16; }
+
+// The coarse block -> tensor index over `first` (live + 1 entries, the last is
+// the block total): at most `buckets` buckets of 2^shift blocks; hint[k] is the
+// tensor that holds block k << shift, and one more entry closes the last bucket.
+template <typename T>
+unsigned make_hints(const std::vector<uint32_t>& first, int buckets, std::vector<T>* hint) {
+    const uint32_t blocks = first.back();
+    const int live = (int)first.size() - 1;
+    unsigned shift = 0;
+    while ((((uint64_t)blocks - 1) >> shift) + 1 > (uint64_t)buckets) ++shift;
+    const uint32_t used = (uint32_t)((((uint64_t)blocks - 1) >> shift) + 1);
+    hint->resize((size_t)used + 1);
+    int l = 0;
+    for (uint32_t k = 0; k < used; ++k) {
+        const uint64_t pos = (uint64_t)k << shift;
+        while ((uint64_t)first[(size_t)l + 1] <= pos) ++l;
+        (*hint)[k] = (T)l;
+    }
+    (*hint)[used] = (T)(live - 1);
+    return shift;
+}
 
 int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_size,
               void* d_workspace, size_t workspace_bytes, void* stream) {
@@ -143,22 +165,28 @@ int run_multi(bool compress, const gact_tensor_desc* descs, int L, int group_siz
         std::memcpy(tab.t, table.data(), (size_t)live * sizeof(gact::TensorArgs));
         std::memcpy(tab.first_block, first.data(), first.size() * sizeof(uint32_t));
         tab.L = live;
+        std::vector<uint8_t> hint;
+        tab.hint_shift = make_hints(first, gact::kInlineHints, &hint);
+        for (size_t k = 0; k < hint.size(); ++k) tab.hint[k >> 2] |= (uint32_t)hint[k] << ((k & 3) * 8);
         return gact_launch_multi_inline(compress ? 1 : 0, &tab, &geo, (unsigned)blocks, stream) == 0
                    ? GACT_OK : GACT_E_HIP;
     }
 
     if (const int rc = refuse_if_capturing(stream)) return rc;
-    const size_t tb = table_bytes(live);
-    std::vector<unsigned char> image(tb + first.size() * sizeof(uint32_t));
+    std::vector<uint32_t> hint;
+    const unsigned shift = make_hints(first, gact::hint_buckets(live), &hint);
+    const size_t tb = table_bytes(live), fb = first_bytes(live);
+    std::vector<unsigned char> image(tb + fb + hint.size() * sizeof(uint32_t));
     std::memcpy(image.data(), table.data(), (size_t)live * sizeof(gact::TensorArgs));
     std::memcpy(image.data() + tb, first.data(), first.size() * sizeof(uint32_t));
+    std::memcpy(image.data() + tb + fb, hint.data(), hint.size() * sizeof(uint32_t));
     // pageable source: the runtime has taken its own copy when this returns
     if (hipMemcpyAsync(d_workspace, image.data(), image.size(), hipMemcpyHostToDevice,
                        (hipStream_t)stream) != hipSuccess)
         return GACT_E_HIP;
-    const gact::TensorArgs* d_table = (const gact::TensorArgs*)d_workspace;
-    const uint32_t* d_first = (const uint32_t*)((const unsigned char*)d_workspace + tb);
-    return gact_launch_multi(compress ? 1 : 0, d_table, d_first, live, &geo, (unsigned)blocks,
+    const unsigned char* base = (const unsigned char*)d_workspace;
+    return gact_launch_multi(compress ? 1 : 0, (const gact::TensorArgs*)base, (const uint32_t*)(base + tb),
+                             (const uint32_t*)(base + tb + fb), shift, &geo, (unsigned)blocks,
                              stream) == 0 ? GACT_OK : GACT_E_HIP;
 }
 
@@ -262,7 +290,7 @@ int gact_decompress(const void* d_packed, const float* d_gmin, const float* d_gs
 
 size_t gact_multi_workspace_bytes(int L) {
     if (L <= 0) return 0;
-    return table_bytes(L) + ((size_t)(L + 1) * sizeof(uint32_t) + 15) / 16 * 16;
+    return table_bytes(L) + first_bytes(L) + ((size_t)gact::hint_buckets(L) + 1) * sizeof(uint32_t);
 }
 
 int gact_compress_multi(const gact_tensor_desc* h_descs, int L, int group_size, void* d_workspace,

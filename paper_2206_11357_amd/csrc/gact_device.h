@@ -53,13 +53,35 @@ struct Geometry {
 // the input's own format.
 constexpr int lds_dwords_per_wave(int dtype) { return dtype == GACT_DT_F32 ? 64 * 32 : 64 * 16; }
 
+// Block -> tensor lookup of a multi-tensor launch.  first_block[l] is the first
+// block of tensor l (one entry per tensor plus the total).  A search over it
+// from scratch is a chain of dependent scalar loads at the start of every
+// block (nine for 400 tensors), during which the block issues nothing else, so
+// the host also lays a coarse index over the blocks: hint[k] is the tensor that
+// holds block k << hint_shift.  Block b then belongs to a tensor in
+// [hint[b >> hint_shift], hint[(b >> hint_shift) + 1]], which for all but the
+// buckets that contain a tensor boundary is a single tensor.
+constexpr int kInlineHints = 128;
+// buckets for a table of L tensors in the workspace: a power of two >= 4 L
+constexpr int hint_buckets(int L) {
+    int h = 64;
+    while (h < 4 * L && h < 16384) h *= 2;
+    return h;
+}
+
 // A launch table small enough to travel in the kernel arguments (4 KB limit).
 constexpr int kInlineTensors = 64;
 struct InlineTable {
     TensorArgs t[kInlineTensors];
     uint32_t   first_block[kInlineTensors + 1];
     int32_t    L;
+    uint32_t   hint_shift;
+    uint32_t   hint[kInlineHints / 4 + 1];   // one byte per bucket, four to a dword (scalar loads fetch dwords)
 };
+// tensor of bucket k in a byte-packed hint array
+__host__ __device__ inline int packed_hint(const uint32_t* hint, uint32_t k) {
+    return (int)((hint[k >> 2] >> ((k & 3u) * 8u)) & 0xFFu);
+}
 
 // One buffer pair of a reduction launch: sensitivity reads a and b; gradient
 // statistics read a (the gradient) and read-modify-write b (the fp32 mean).
@@ -106,7 +128,8 @@ extern "C" int gact_launch_grad_stats(const gact::ReduceArgs* d_table, const uin
 extern "C" int gact_launch_multi_inline(int compress, const gact::InlineTable* tab,
                                         const gact::Geometry* geo, unsigned blocks, void* stream);
 extern "C" int gact_launch_multi(int compress, const gact::TensorArgs* d_table,
-                                 const uint32_t* d_first_block, int L,
-                                 const gact::Geometry* geo, unsigned blocks, void* stream);
+                                 const uint32_t* d_first_block, const uint32_t* d_hint,
+                                 unsigned hint_shift, const gact::Geometry* geo, unsigned blocks,
+                                 void* stream);
 
 #endif

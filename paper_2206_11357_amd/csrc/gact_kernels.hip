@@ -432,12 +432,21 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
     float inv = 0.0f, step = 0.0f;
     if (range >= 0x1p-100f) { inv = Bf / range; step = range / Bf; }
 
-    const bool lane_live = !EDGE || my0 < ne;
-    const int grp_in_tile = EDGE ? lane / geo.lpg : lane >> geo.lpg_shift;
-    if (lane_live && lane == grp_in_tile * geo.lpg) {
-        const int64_t g = tile * (int64_t)geo.groups_per_tile + grp_in_tile;
-        t.gmin[g] = mn;
-        t.gscale[g] = step;
+    // Minimum and step of every group of the tile.  All lanes of a group hold the
+    // same pair.  Stored from the first lane of each group, the values would leave
+    // from lanes lpg apart, and a store whose active lanes are scattered over the
+    // wavefront goes to memory as one small request per lane (with 4 lanes per
+    // group those requests cost 7 % of the compressor's time).  So the pairs are
+    // first gathered into the low lanes (two ds_bpermute on the LDS crossbar: lane
+    // i takes minimum and step of group i from lane i * lpg) and leave as two
+    // contiguous runs.  The gathers are issued here and their results stored
+    // after the codes, so that nothing waits for the LDS round trip.
+    const int64_t g0 = tile * (int64_t)geo.groups_per_tile;        // first group of the tile
+    float group_mn = mn, group_step = step;
+    if (geo.lpg > 1) {
+        const int src = lane * geo.lpg;                            // lanes past the last group read a wrapped lane, unused
+        group_mn = lane_read(mn, src);
+        group_step = lane_read(step, src);
     }
 
     // stochastic rounding + packing: 8 elements per Philox block.
@@ -502,6 +511,13 @@ __device__ __forceinline__ void compress_tile(const TensorArgs& t, const Geometr
     uint32_t out[BITS];
 #pragma unroll
     for (int w = 0; w < BITS; ++w) out[w] = kBiasWord - acc[w];
+
+    if (lane < geo.groups_per_tile && (!EDGE || lane * geo.lpg * kPerLane < ne)) {
+        float* gm = t.gmin + g0;                                   // uniform bases, lane offsets
+        float* gs = t.gscale + g0;
+        gm[lane] = group_mn;
+        gs[lane] = group_step;
+    }
 
     // lane i owns dwords [i*BITS, (i+1)*BITS) of the tile's packed words
     const int64_t word0 = (e0 >> 5) * BITS + (int64_t)lane * BITS;
@@ -720,9 +736,15 @@ __global__ __launch_bounds__(kBlockThreads) void compress_sum_kernel(TensorArgs 
 }
 
 // Multi-tensor: block b belongs to the tensor l with first_block[l] <= b <
-// first_block[l+1].
-__device__ __forceinline__ int find_tensor(const uint32_t* first_block, int L, uint32_t b) {
-    int lo = 0, hi = L;                 // invariant: first_block[lo] <= b < first_block[hi]
+// first_block[l+1]; hint[] narrows the search to the tensors that overlap the
+// block's bucket (see gact_device.h), usually one.
+template <bool PACKED>
+__device__ __forceinline__ int find_tensor(const uint32_t* first_block, const uint32_t* hint, uint32_t shift,
+                                           uint32_t b) {
+    const uint32_t k = b >> shift;
+    int lo = PACKED ? packed_hint(hint, k) : (int)hint[k];
+    int hi = (PACKED ? packed_hint(hint, k + 1) : (int)hint[k + 1]) + 1;
+    // invariant: first_block[lo] <= b < first_block[hi]
     while (hi - lo > 1) {
         const int mid = (lo + hi) >> 1;
         if (first_block[mid] <= b) lo = mid; else hi = mid;
@@ -732,11 +754,11 @@ __device__ __forceinline__ int find_tensor(const uint32_t* first_block, int L, u
 
 // Table in device memory (the caller's workspace): any number of tensors.
 template <bool COMPRESS>
-__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void multi_kernel(const TensorArgs* __restrict__ table,
-                                                              const uint32_t* __restrict__ first_block,
-                                                              int L, Geometry geo) {
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void multi_kernel(
+    const TensorArgs* __restrict__ table, const uint32_t* __restrict__ first_block,
+    const uint32_t* __restrict__ hint, uint32_t hint_shift, Geometry geo) {
     const uint32_t b = blockIdx.x;
-    const int l = find_tensor(first_block, L, b);
+    const int l = find_tensor<false>(first_block, hint, hint_shift, b);
     const TensorArgs t = table[l];
     run_block<COMPRESS>(t, geo, (int64_t)(b - first_block[l]));
 }
@@ -744,9 +766,10 @@ __global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(8
 // Table passed by value in the kernel arguments: up to kInlineTensors tensors,
 // no upload and no host synchronisation before the launch.
 template <bool COMPRESS>
-__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void multi_inline_kernel(InlineTable tab, Geometry geo) {
+__global__ __launch_bounds__(kBlockThreads) __attribute__((amdgpu_waves_per_eu(8, 8))) void multi_inline_kernel(
+    InlineTable tab, Geometry geo) {
     const uint32_t b = blockIdx.x;
-    const int l = find_tensor(tab.first_block, tab.L, b);
+    const int l = find_tensor<true>(tab.first_block, tab.hint, tab.hint_shift, b);
     run_block<COMPRESS>(tab.t[l], geo, (int64_t)(b - tab.first_block[l]));
 }
 
@@ -786,15 +809,16 @@ extern "C" int gact_launch_multi_inline(int compress, const gact::InlineTable* t
 }
 
 extern "C" int gact_launch_multi(int compress, const gact::TensorArgs* d_table,
-                                 const uint32_t* d_first_block, int L, const gact::Geometry* geo,
-                                 unsigned blocks, void* stream) {
+                                 const uint32_t* d_first_block, const uint32_t* d_hint,
+                                 unsigned hint_shift, const gact::Geometry* geo, unsigned blocks,
+                                 void* stream) {
     hipStream_t s = (hipStream_t)stream;
     const unsigned lds = compress ? 4u * gact::kWavesPerBlk * (unsigned)geo->lds_wave_dwords : 0u;
     if (compress)
         hipLaunchKernelGGL(gact::multi_kernel<true>, dim3(blocks), dim3(gact::kBlockThreads), lds, s,
-                           d_table, d_first_block, L, *geo);
+                           d_table, d_first_block, d_hint, hint_shift, *geo);
     else
         hipLaunchKernelGGL(gact::multi_kernel<false>, dim3(blocks), dim3(gact::kBlockThreads), lds, s,
-                           d_table, d_first_block, L, *geo);
+                           d_table, d_first_block, d_hint, hint_shift, *geo);
     return hipGetLastError() == hipSuccess ? 0 : -1;
 }
