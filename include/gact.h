@@ -75,8 +75,10 @@ enum {
     GACT_E_GROUP  = -3,  /* group_size not a multiple of 32 in [32, 1024] */
     GACT_E_BUDGET = -4,  /* avg_bit_budget < 1 or NaN: no feasible scheme */
     GACT_E_HIP    = -5,  /* the HIP runtime refused the launch or copy */
-    GACT_E_CAPTURE = -6  /* the stream is being captured into a HIP graph and this call
+    GACT_E_CAPTURE = -6, /* the stream is being captured into a HIP graph and this call
                             would have to upload a table from host memory */
+    GACT_E_SCRATCH = -7  /* gact_compress_footprint_noalloc: the tensor needs more than the
+                            library's static scratch area */
 };
 
 /* ceil(n / group_size); 0 when n <= 0 or group_size <= 0. */
@@ -241,6 +243,31 @@ int gact_compress_footprint(const void *d_x, gact_dtype dtype, int64_t n, int gr
                             int bits, uint64_t seed, void *d_packed, float *d_gmin,
                             float *d_gscale, int n_samples, double *d_footprint,
                             void *d_workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * gact_compress_footprint for callers that cannot allocate device memory and
+ * so cannot bring a workspace: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  The per-tile partial sums go to a
+ * scratch area of GACT_NOALLOC_SCRATCH_BYTES that is part of the library's
+ * device image (each GPU the library runs on holds one copy until the process
+ * ends); the call allocates and frees nothing.  Same arguments, results and
+ * error codes as gact_compress_footprint without the workspace pair; results
+ * are byte-identical to that call's.
+ *   Limit: one 8-byte partial per tile of 2048 elements (63 * 32 ... 64 * 32
+ *   elements when group_size / 32 is not a power of two), i.e. up to
+ *   536,870,912 elements for power-of-two group sizes.  A larger n returns
+ *   GACT_E_SCRATCH and enqueues nothing.
+ *   All calls on one GPU share that GPU's area: two calls whose kernels may
+ *   overlap in time (different streams, or graph launches in flight together)
+ *   race on it and must be ordered by the caller.  The area keeps the last
+ *   call's contents; nothing in it has to start at zero, because every partial
+ *   a call reads was written by that call's own compress kernel.
+ */
+#define GACT_NOALLOC_SCRATCH_BYTES (2u << 20)
+int gact_compress_footprint_noalloc(const void *d_x, gact_dtype dtype, int64_t n, int group_size,
+                                    int bits, uint64_t seed, void *d_packed, float *d_gmin,
+                                    float *d_gscale, int n_samples, double *d_footprint,
+                                    void *stream);
 
 /*
  * Variance alert (host only): V(b) = sum_l c_l S(b_l) (Thm. 2) against the

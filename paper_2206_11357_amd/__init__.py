@@ -27,6 +27,8 @@ GACT_E_GROUP = -3
 GACT_E_BUDGET = -4
 GACT_E_HIP = -5
 GACT_E_CAPTURE = -6
+GACT_E_SCRATCH = -7
+GACT_NOALLOC_SCRATCH_BYTES = 2 << 20
 
 EXPORTS = (
     "gact_num_groups", "gact_packed_bytes", "gact_error_string", "gact_compress",
@@ -34,7 +36,7 @@ EXPORTS = (
     "gact_decompress_multi", "gact_allocate_bits", "gact_reduce_workspace_bytes",
     "gact_sensitivity", "gact_grad_stats_update", "gact_variance_alert",
     "gact_allocate_bits_levels", "gact_footprint", "gact_compress_footprint",
-    "gact_compress_footprint_workspace_bytes",
+    "gact_compress_footprint_workspace_bytes", "gact_compress_footprint_noalloc",
 )
 GACT_BITS_UNCOMPRESSED = 32
 
@@ -105,6 +107,8 @@ def _load() -> ctypes.CDLL:
     lib.gact_compress_footprint.argtypes = [vp, i32, i64, i32, i32, ctypes.c_uint64, vp, vp, vp, i32, vp,
                                             vp, sz, vp]
     lib.gact_compress_footprint.restype = i32
+    lib.gact_compress_footprint_noalloc.argtypes = [vp, i32, i64, i32, i32, ctypes.c_uint64, vp, vp, vp, i32, vp, vp]
+    lib.gact_compress_footprint_noalloc.restype = i32
     lib.gact_variance_alert.argtypes = [vp, vp, i32, ctypes.c_double, ctypes.c_double, vp]
     lib.gact_variance_alert.restype = i32
     return lib
@@ -376,6 +380,19 @@ def gact_compress_footprint(x: torch.Tensor, group_size: int, bits: int, seed: i
     if rc != GACT_OK:
         raise GactError(rc, "gact_compress_footprint")
     return packed, gmin, gscale, footprint
+
+
+def gact_compress_footprint_noalloc(x: torch.Tensor, group_size: int, bits: int, seed: int, n_samples: int,
+                                    packed: torch.Tensor, gmin: torch.Tensor, gscale: torch.Tensor,
+                                    footprint: torch.Tensor, stream=None) -> None:
+    """gact_compress_footprint on the library's own scratch area: every buffer comes from the
+    caller and neither the call nor this wrapper allocates."""
+    rc = lib.gact_compress_footprint_noalloc(x.data_ptr(), dtype_code(x.dtype), x.numel(), group_size, bits,
+                                             seed & (2**64 - 1), packed.data_ptr(), gmin.data_ptr(),
+                                             gscale.data_ptr(), n_samples, footprint.data_ptr(),
+                                             _stream(stream))
+    if rc != GACT_OK:
+        raise GactError(rc, "gact_compress_footprint_noalloc")
 
 
 def gact_variance_alert(sensitivity, bits, grad_var: float, threshold: float):

@@ -5,12 +5,19 @@
 
 #include <cmath>
 #include <cstring>
+#include <mutex>
 #include <queue>
 #include <algorithm>
 #include <vector>
 
 #include "gact.h"
 #include "gact_device.h"
+
+// Scratch area of gact_compress_footprint_noalloc: device memory that is part
+// of the library's code object, one copy per GPU, held until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; kernels get
+// the address that call returns.
+static __device__ __align__(256) unsigned char scratch[GACT_NOALLOC_SCRATCH_BYTES];
 
 namespace {
 
@@ -234,6 +241,52 @@ int stage_reduction(const std::vector<gact::ReduceArgs>& bufs, void* d_workspace
     return GACT_OK;
 }
 
+// Address of `scratch` on the current device, looked up once per device.
+int scratch_of_current_device(void** out) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex lock;
+    static void* address[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return GACT_E_HIP;
+    std::lock_guard<std::mutex> hold(lock);
+    if (!address[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return GACT_E_HIP;
+        address[dev] = p;
+    }
+    *out = address[dev];
+    return GACT_OK;
+}
+
+// gact_compress_footprint on a caller workspace, or (limited = true) on the
+// library's own scratch area, where a tensor that needs more is refused.
+int compress_footprint(const void* d_x, gact_dtype dtype, int64_t n, int group_size, int bits,
+                       uint64_t seed, void* d_packed, float* d_gmin, float* d_gscale, int n_samples,
+                       double* d_footprint, void* d_workspace, size_t workspace_bytes, bool limited,
+                       void* stream) {
+    if (!bits_ok(bits)) return GACT_E_BITS;
+    if (!group_ok(group_size)) return GACT_E_GROUP;
+    if (n_samples < 0 || n_samples > 32768 || !d_footprint || !aligned(d_footprint, 8)) return GACT_E_ARG;
+    gact::Geometry geo = make_geometry(group_size);
+    geo.lds_wave_dwords = gact::lds_dwords_per_wave((int)dtype);
+    gact::TensorArgs t;
+    const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, 0, bits,
+                             (int)dtype, geo, &t);
+    if (rc != GACT_OK) return rc;
+    if (n == 0)
+        return gact_launch_zero(d_footprint, 1 + n_samples, stream) == 0 ? GACT_OK : GACT_E_HIP;
+    const size_t need = (size_t)tiles_for(n, geo) * sizeof(double);       // one partial sum per tile
+    if (!d_workspace || !aligned(d_workspace, 16) || workspace_bytes < need)
+        return limited ? GACT_E_SCRATCH : GACT_E_ARG;
+    const int64_t blocks = blocks_for(true, t, geo);
+    if (blocks > 0x7FFFFFFFll) return GACT_E_ARG;
+    if (gact_launch_compress_sum(&t, &geo, (unsigned)blocks, (double*)d_workspace, stream) != 0)
+        return GACT_E_HIP;
+    const gact::ReduceArgs r{d_x, nullptr, n, (int32_t)dtype, 0};
+    return gact_launch_footprint_finish(&r, (unsigned)tiles_for(n, geo), (double*)d_workspace, n_samples,
+                                        d_footprint, stream) == 0 ? GACT_OK : GACT_E_HIP;
+}
+
 }  // namespace
 
 extern "C" {
@@ -258,6 +311,7 @@ const char* gact_error_string(int code) {
         case GACT_E_BUDGET: return "avg_bit_budget must be >= 1";
         case GACT_E_HIP: return "HIP runtime error";
         case GACT_E_CAPTURE: return "the stream is capturing a HIP graph and this call needs a table upload from host memory";
+        case GACT_E_SCRATCH: return "the tensor needs more than the library's static scratch area (GACT_NOALLOC_SCRATCH_BYTES)";
         default: return "unknown error";
     }
 }
@@ -390,27 +444,18 @@ int gact_compress_footprint(const void* d_x, gact_dtype dtype, int64_t n, int gr
                             uint64_t seed, void* d_packed, float* d_gmin, float* d_gscale,
                             int n_samples, double* d_footprint, void* d_workspace,
                             size_t workspace_bytes, void* stream) {
-    if (!bits_ok(bits)) return GACT_E_BITS;
-    if (!group_ok(group_size)) return GACT_E_GROUP;
-    if (n_samples < 0 || n_samples > 32768 || !d_footprint || !aligned(d_footprint, 8)) return GACT_E_ARG;
-    gact::Geometry geo = make_geometry(group_size);
-    geo.lds_wave_dwords = gact::lds_dwords_per_wave((int)dtype);
-    gact::TensorArgs t;
-    const int rc = make_args(true, d_x, d_packed, d_gmin, d_gscale, nullptr, n, seed, 0, bits,
-                             (int)dtype, geo, &t);
-    if (rc != GACT_OK) return rc;
-    if (n == 0)
-        return gact_launch_zero(d_footprint, 1 + n_samples, stream) == 0 ? GACT_OK : GACT_E_HIP;
-    if (!d_workspace || !aligned(d_workspace, 16) ||
-        workspace_bytes < gact_compress_footprint_workspace_bytes(n, group_size))
-        return GACT_E_ARG;
-    const int64_t blocks = blocks_for(true, t, geo);
-    if (blocks > 0x7FFFFFFFll) return GACT_E_ARG;
-    if (gact_launch_compress_sum(&t, &geo, (unsigned)blocks, (double*)d_workspace, stream) != 0)
-        return GACT_E_HIP;
-    const gact::ReduceArgs r{d_x, nullptr, n, (int32_t)dtype, 0};
-    return gact_launch_footprint_finish(&r, (unsigned)tiles_for(n, geo), (double*)d_workspace, n_samples, d_footprint,
-                                        stream) == 0 ? GACT_OK : GACT_E_HIP;
+    return compress_footprint(d_x, dtype, n, group_size, bits, seed, d_packed, d_gmin, d_gscale,
+                              n_samples, d_footprint, d_workspace, workspace_bytes, false, stream);
+}
+
+int gact_compress_footprint_noalloc(const void* d_x, gact_dtype dtype, int64_t n, int group_size,
+                                    int bits, uint64_t seed, void* d_packed, float* d_gmin,
+                                    float* d_gscale, int n_samples, double* d_footprint,
+                                    void* stream) {
+    void* area = nullptr;
+    if (const int rc = scratch_of_current_device(&area)) return rc;
+    return compress_footprint(d_x, dtype, n, group_size, bits, seed, d_packed, d_gmin, d_gscale,
+                              n_samples, d_footprint, area, GACT_NOALLOC_SCRATCH_BYTES, true, stream);
 }
 
 int gact_variance_alert(const float* h_sensitivity, const int32_t* h_bits, int L, double grad_var,
