@@ -134,26 +134,36 @@ def gact_multi_workspace_bytes(L: int) -> int:
     return int(lib.gact_multi_workspace_bytes(L))
 
 
+_DTYPE_CODES = {torch.float32: GACT_F32, torch.bfloat16: GACT_BF16}
+
+
 def dtype_code(dtype: torch.dtype) -> int:
-    if dtype == torch.float32:
-        return GACT_F32
-    if dtype == torch.bfloat16:
-        return GACT_BF16
-    raise TypeError("gact handles float32 and bfloat16 tensors, got %s" % dtype)
+    try:
+        return _DTYPE_CODES[dtype]
+    except KeyError:
+        raise TypeError("gact handles float32 and bfloat16 tensors, got %s" % dtype) from None
 
 
 def _stream(stream) -> int:
+    """hipStream_t as an integer: None = torch's current stream; a torch stream; or the integer itself
+    (a call site that issues many calls resolves the stream once and passes the handle)."""
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
+    if type(stream) is int:
+        return stream
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
 
 
-def _flat(x: torch.Tensor) -> torch.Tensor:
+def _check(x: torch.Tensor) -> torch.Tensor:
     if not x.is_cuda:
         raise ValueError("gact needs device tensors")
     if not x.is_contiguous():
         raise ValueError("gact needs contiguous tensors")
-    return x.view(-1)
+    return x
+
+
+def _flat(x: torch.Tensor) -> torch.Tensor:
+    return _check(x).view(-1)
 
 
 def alloc_compressed(n: int, group_size: int, bits: int, device) -> Tuple[torch.Tensor, ...]:
@@ -170,8 +180,7 @@ def gact_compress(x: torch.Tensor, group_size: int, bits: int, seed: int,
                   packed: Optional[torch.Tensor] = None, gmin: Optional[torch.Tensor] = None,
                   gscale: Optional[torch.Tensor] = None, stream=None):
     """Compress one tensor; returns (packed, gmin, gscale) device tensors."""
-    x = _flat(x)
-    n = x.numel()
+    n = _check(x).numel()
     if packed is None:
         packed, gmin, gscale = alloc_compressed(n, max(group_size, 1), bits if bits > 0 else 1,
                                                 x.device)
@@ -190,11 +199,45 @@ def gact_decompress(packed: torch.Tensor, gmin: torch.Tensor, gscale: torch.Tens
     if y is None:
         y = torch.empty(n, dtype=dtype, device=packed.device)
     rc = lib.gact_decompress(packed.data_ptr(), gmin.data_ptr(), gscale.data_ptr(), n,
-                             group_size, bits, _flat(y).data_ptr(), dtype_code(y.dtype),
+                             group_size, bits, _check(y).data_ptr(), dtype_code(y.dtype),
                              _stream(stream))
     if rc != GACT_OK:
         raise GactError(rc, "gact_decompress")
     return y
+
+
+class PreparedCall:
+    """One single-tensor call with its arguments marshalled once: ``call(stream_handle)`` enqueues it
+    on that stream (an integer hipStream_t, e.g. ``torch.cuda.current_stream().cuda_stream``).  For
+    loops that issue the same call many times (a serving loop, one call per saved tensor and step):
+    nothing is looked up or converted per call.  The object keeps the tensors alive."""
+    __slots__ = ("_fn", "_args", "_name", "_keep")
+
+    def __init__(self, fn, name, args, keep):
+        self._fn, self._name, self._args, self._keep = fn, name, args, keep
+
+    def __call__(self, stream_handle: int = 0) -> None:
+        rc = self._fn(*self._args, stream_handle)
+        if rc != GACT_OK:
+            raise GactError(rc, self._name)
+
+
+def prepare_compress(x: torch.Tensor, group_size: int, bits: int, seed: int, packed: torch.Tensor,
+                     gmin: torch.Tensor, gscale: torch.Tensor) -> PreparedCall:
+    """gact_compress(x, ...) into the given buffers, as a PreparedCall."""
+    vp = ctypes.c_void_p
+    args = (vp(_check(x).data_ptr()), dtype_code(x.dtype), ctypes.c_int64(x.numel()), group_size, bits,
+            ctypes.c_uint64(seed & (2**64 - 1)), vp(packed.data_ptr()), vp(gmin.data_ptr()), vp(gscale.data_ptr()))
+    return PreparedCall(lib.gact_compress, "gact_compress", args, (x, packed, gmin, gscale))
+
+
+def prepare_decompress(packed: torch.Tensor, gmin: torch.Tensor, gscale: torch.Tensor, n: int,
+                       group_size: int, bits: int, y: torch.Tensor) -> PreparedCall:
+    """gact_decompress(...) into y, as a PreparedCall."""
+    vp = ctypes.c_void_p
+    args = (vp(packed.data_ptr()), vp(gmin.data_ptr()), vp(gscale.data_ptr()), ctypes.c_int64(n), group_size, bits,
+            vp(_check(y).data_ptr()), dtype_code(y.dtype))
+    return PreparedCall(lib.gact_decompress, "gact_decompress", args, (packed, gmin, gscale, y))
 
 
 # ---------------------------------------------------------------- multi tensor

@@ -518,3 +518,31 @@ def test_multi_tensor_three_thousand_tiny_tensors(gact):
             x = syn.f32_to_bf16_bits(x)
         specs.append((x, int(rng.choice([1, 2, 4, 8])), k))
     multi_case(gact, specs, 64)
+
+
+def test_prepared_calls_give_the_same_bytes_as_the_plain_calls(gact):
+    """A call marshalled once and issued repeatedly (PreparedCall) is the same C call: same bytes, on the
+    default stream and on a side stream."""
+    n, G, bits, seed = 3 * 8192 + 321, 128, 4, 77
+    x_np = syn.f32_to_bf16_bits(syn.draw_numpy(syn.NORMAL, n, 31))
+    x = to_device(x_np)
+    ref = gact.gact_compress(x, G, bits, seed)
+    y_ref = gact.gact_decompress(*ref, n, G, bits, dtype=x.dtype)
+    bufs = gact.alloc_compressed(n, G, bits, x.device)
+    y = torch.empty_like(x)
+    comp = gact.prepare_compress(x, G, bits, seed, *bufs)
+    dec = gact.prepare_decompress(*bufs, n, G, bits, y)
+    side = torch.cuda.Stream()
+    for stream in (torch.cuda.current_stream(), side):
+        for t in bufs:
+            t.view(torch.uint8).fill_(0)
+        y.view(torch.int16).fill_(0)
+        torch.cuda.synchronize()
+        comp(stream.cuda_stream)
+        dec(stream.cuda_stream)
+        stream.synchronize()
+        for got, want in zip(bufs, ref):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8))
+        assert torch.equal(y.view(torch.int16), y_ref.view(torch.int16))
+    p_ref, mn_ref, sc_ref = oracle.compress(x_np, G, bits, seed)
+    assert np.array_equal(to_host(bufs[0]), p_ref)
