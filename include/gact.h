@@ -273,6 +273,8 @@ int gact_compress_footprint_noalloc(const void *d_x, gact_dtype dtype, int64_t n
  * Variance alert (host only): V(b) = sum_l c_l S(b_l) (Thm. 2) against the
  * gradient variance.  Writes V / grad_var to *h_ratio (may be NULL) and
  * returns 1 if it exceeds `threshold`, 0 if not, a negative code on error.
+ * b_l in {1, 2, 4, 8, GACT_BITS_UNCOMPRESSED}: a tensor that
+ * gact_allocate_bits_levels left uncompressed counts with S(32) = (2^32-1)^-2.
  */
 int gact_variance_alert(const float *h_sensitivity, const int32_t *h_bits, int L,
                         double grad_var, double threshold, double *h_ratio);

@@ -434,8 +434,10 @@ int gact_oracle_variance_ratio(const float *c, const int32_t *bits, int L,
     double V = 0.0;
     for (int l = 0; l < L; ++l) {
         int b = bits[l];
-        if (!(b == 1 || b == 2 || b == 4 || b == 8) || !(c[l] >= 0.0f)) return -1;
-        double B = (double)((1 << b) - 1);
+        /* 32 = a tensor the allocator left uncompressed (Sec. 6.1); S(b) = (2^b - 1)^-2
+           of Sec. 4.1 evaluated at b = 32 */
+        if (!(b == 1 || b == 2 || b == 4 || b == 8 || b == 32) || !(c[l] >= 0.0f)) return -1;
+        double B = ldexp(1.0, b) - 1.0;
         V += (double)c[l] / (B * B);
     }
     if (!(grad_var > 0.0)) return -1;

@@ -55,6 +55,15 @@ def lines():
         sha(c), sha(bits.astype(np.int32)), ",".join(str(int((bits == k).sum())) for k in (1, 2, 4, 8)))
     yield "philox_counter_0_1_2_3_key_4_5 words=%s" % ",".join(
         "%08x" % int(w) for w in oracle.philox4x32_10([0, 1, 2, 3], [4, 5]))
+    # three more blocks of the generator: counter and key all zero, all ones, and the hexadecimal
+    # digits of pi (the inputs for which the generator's authors publish known answers)
+    ones = 0xFFFFFFFF
+    for name, ctr, key in (
+        ("philox_counter_zero_key_zero", [0, 0, 0, 0], [0, 0]),
+        ("philox_counter_ones_key_ones", [ones] * 4, [ones] * 2),
+        ("philox_counter_pi_key_pi", [0x243F6A88, 0x85A308D3, 0x13198A2E, 0x03707344], [0xA4093822, 0x299F31D0]),
+    ):
+        yield "%s words=%s" % (name, ",".join("%08x" % int(w) for w in oracle.philox4x32_10(ctr, key)))
 
 
 if __name__ == "__main__":

@@ -165,6 +165,23 @@ def test_variance_alert_matches_the_oracle_and_reports_errors():
     assert gact.gact_reduce_workspace_bytes(3, 10000) >= 3 * 32 + 16 + 2 * 8 * (10000 // 4096 + 3)
 
 
+def test_variance_alert_takes_the_allocator_s_uncompressed_level():
+    """Sec. 6.1 keeps the most sensitive tensors at 32 bits; the alert of Sec. 4.2 must accept exactly
+    what gact_allocate_bits_levels hands out."""
+    rng = np.random.default_rng(9)
+    c = rng.lognormal(0, 3, 24).astype(np.float32)
+    numel = rng.integers(1000, 100000, 24).astype(np.int64)
+    bits = gact.gact_allocate_bits_levels(c, numel, 6.0, [1, 2, 4, 8, 32])
+    assert (bits == 32).any() and (bits < 32).any()
+    alert, ratio = gact.gact_variance_alert(c, bits, 2.0, 1e-3)
+    assert ratio == pytest.approx(oracle.variance_ratio(c, bits, 2.0), rel=1e-12)
+    # closed form, S(b) = (2^b - 1)^-2 of Sec. 4.1 in exact rationals
+    from fractions import Fraction
+    exact = sum(Fraction(float(cl)) / (2 ** int(b) - 1) ** 2 for cl, b in zip(c, bits)) / 2
+    assert ratio == pytest.approx(float(exact), rel=1e-12)
+    assert alert == (float(exact) > 1e-3)
+
+
 @pytest.mark.parametrize("seed", range(40))
 def test_level_set_allocator_is_identical_to_the_oracle(seed):
     rng = np.random.default_rng(1000 + seed)
