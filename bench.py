@@ -676,6 +676,8 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
     res["compress_4bit"] = run(Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14), steps, warmup)
     res["compress_2bit"] = run(Controller(params, group_size=256, bits=2, seed=0, min_numel=1 << 14), steps, warmup)
     res["compress_4bit_swap"] = run(Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14, swap=True), steps, warmup)
+    res["compress_4bit_swap_resident_256MB"] = run(Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14,
+                                                              swap=True, resident_bytes=256 << 20), steps, warmup)
     ref = res["no_hooks"]
     for k, r in res.items():
         r["activation_memory_ratio"] = round(ref["peak_activation_MB"] / max(r["peak_activation_MB"], 1e-9), 2)

@@ -1,70 +1,122 @@
 """Saved-tensor hooks that route autograd's saved activations through the GACT
 compressor (arXiv 2206.11357, Sec. 5: one hook interface for all operators;
-Sec. 5.2: parameters and tensors that need no gradient are not quantized;
-Sec. 5.3: optional swap of the *compressed* tensors to host memory on two side
-streams (one out, one in), with prefetch during the backward pass).
+Sec. 5.2: parameters and tensors that need no gradient are not quantized, a
+tensor saved by several operators is quantized once; Sec. 5.3: optional swap of
+the *compressed* tensors to host memory on two side streams (one out, one in),
+with prefetch during the backward pass).
 
-This is glue around the library's kernels: ``pack`` calls ``gact_compress``,
-``unpack`` calls ``gact_decompress``.  Per-tensor bit widths and the
-replayable per-tensor seeds r_l of Alg. 1 come from the ``Controller``.
+This is glue around the library's kernels and does no arithmetic of its own.
+The saved tensors of one iteration are compressed in batches, one
+``gact_compress_multi`` launch per batch (the multi-tensor launch exists for
+exactly this: many tensors per iteration), into one buffer per batch; the
+backward pass decompresses a few tensors ahead of use with one
+``gact_decompress_multi`` launch, and swapping moves one buffer per batch.
+Per-tensor bit widths and the replayable per-tensor seeds r_l of Alg. 1 come
+from the ``Controller``.
 """
 from __future__ import annotations
 
-from dataclasses import dataclass
+import ctypes
 from typing import Callable, Dict, List, Optional, Sequence
 
 import numpy as np
 import torch
 
-from . import (GACT_BITS_UNCOMPRESSED, gact_allocate_bits_levels, gact_compress, gact_compress_footprint,
-               gact_decompress, gact_num_groups, gact_packed_bytes, gact_sensitivity)
+from . import (GACT_BITS_UNCOMPRESSED, GACT_OK, GactError, TensorDesc, dtype_code, gact_allocate_bits_levels,
+               gact_multi_workspace_bytes, gact_num_groups, gact_packed_bytes, gact_sensitivity, lib)
+
+_MASK64 = (1 << 64) - 1
+_MAX_BATCH = 64            # a launch table of at most 64 tensors travels in the kernel arguments
 
 
-@dataclass
+def _mix64(z: int) -> int:
+    """splitmix64 finaliser: spreads (seed, iteration) over the 64-bit Philox key space."""
+    z = (z + 0x9E3779B97F4A7C15) & _MASK64
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK64
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK64
+    return z ^ (z >> 31)
+
+
 class _Packed:
-    index: int                 # position among the context tensors of this iteration
-    shape: torch.Size
-    dtype: torch.dtype
-    n: int
-    bits: int
-    packed: Optional[torch.Tensor]
-    gmin: Optional[torch.Tensor]
-    gscale: Optional[torch.Tensor]
-    blob: Optional[torch.Tensor] = None   # swap mode: the one device buffer the three above are views of
-    host: Optional[torch.Tensor] = None   # pinned copy of the blob when swapped out
-    out_event: Optional[torch.cuda.Event] = None
-    in_event: Optional[torch.cuda.Event] = None
+    """What autograd holds instead of a saved tensor."""
+    __slots__ = ("index", "shape", "dtype", "n", "bits", "seed", "x", "version", "batch", "off", "y", "done")
+
+    def __init__(self, index, shape, dtype, n, bits, seed, x):
+        self.index, self.shape, self.dtype, self.n, self.bits, self.seed = index, shape, dtype, n, bits, seed
+        self.x = x                 # the tensor itself until its batch has been compressed
+        self.version = x._version
+        self.batch = None          # _Batch once compressed
+        self.off = None            # (packed, gmin, gscale) byte offsets inside the batch's buffer
+        self.y = None              # decompressed ahead of use
+        self.done = False          # handed back to autograd at least once
+
+
+class _Batch:
+    """Tensors compressed by one launch into one buffer.  Holds no reference to its handles (they
+    point here): a cycle would keep the buffer alive until the garbage collector runs."""
+    __slots__ = ("count", "blob", "nbytes", "host", "out_event", "in_event", "remaining")
+
+    def __init__(self, count, blob):
+        self.count, self.blob, self.nbytes = count, blob, blob.numel()
+        self.host = None           # pinned copy once swapped out
+        self.out_event = None
+        self.in_event = None
+        self.remaining = count     # tensors not yet decompressed since the buffer came (back) to the device
 
 
 class Controller:
     """Holds the compression scheme b = (b_l), the seeds (r_l) and the
-    sensitivities c_l of the context tensors of one model."""
+    sensitivities c_l of the context tensors of one model.
+
+    batch_tensors / batch_bytes   a batch is compressed when it holds this many tensors or bytes of
+                                  uncompressed activations (they stay alive until then)
+    ahead_tensors / ahead_bytes   the backward pass decompresses up to this much ahead of use
+    swap, resident_bytes          swap compressed batches to pinned host memory, except the most recent
+                                  `resident_bytes` of them, which the backward pass needs first
+    """
 
     def __init__(self, params: Sequence[torch.Tensor] = (), group_size: int = 256, bits: int = 4,
-                 seed: int = 0, min_numel: int = 1024, swap: bool = False, dedup: bool = False):
+                 seed: int = 0, min_numel: int = 1024, swap: bool = False, dedup: bool = False,
+                 batch_tensors: int = 32, batch_bytes: int = 128 << 20, ahead_tensors: int = 32,
+                 ahead_bytes: int = 128 << 20, resident_bytes: int = 0):
         self.group_size = group_size
         self.default_bits = bits
         self.base_seed = seed
         self.min_numel = min_numel
         self.swap = swap
-        # dedup: a tensor saved by several operators is compressed once.  The data pointer
-        # alone cannot identify it (the allocator hands a freed activation's address to the
-        # next one), so candidates are confirmed by their footprint: sum + sampled points
-        # (Sec. 5.2), taken by the compressor in the same read; a duplicate's new copy is dropped.
+        # dedup: a tensor that several operators save (the input shared by the Q, K and V projections)
+        # is compressed once.  While a tensor waits in the current batch the controller holds it, so
+        # "same storage, same version counter" identifies it exactly; no footprint has to be computed.
         self.dedup = dedup
+        self.batch_tensors = max(1, min(batch_tensors, _MAX_BATCH))
+        self.batch_bytes = batch_bytes
+        self.ahead_tensors = max(1, min(ahead_tensors, _MAX_BATCH))
+        self.ahead_bytes = ahead_bytes
+        self.resident_bytes = resident_bytes
         self.param_ptrs = {p.data_ptr() for p in params}
         self.bits: Dict[int, int] = {}            # index l -> b_l
         self.seed_override: Dict[int, int] = {}   # index l -> r_l (Alg. 1 reseeds one tensor)
         self.numel: List[int] = []                # D_l seen in the last iteration
         self.sensitivity: Optional[np.ndarray] = None
-        self._index = 0
-        self._live: Dict[int, _Packed] = {}
-        self._by_storage: Dict[tuple, tuple] = {}   # (ptr, numel, dtype) -> (handle, footprint)
+        # Fresh compressor randomness every training step (the convergence argument of Sec. 3 needs
+        # it); Alg. 1 needs the same (r_l) in its passes, so the counter is frozen while it runs.
+        self.iteration = -1
+        self._frozen = False
+        self._iter_key = _mix64(seed)
+        self._handles: List[_Packed] = []         # by index, this iteration
+        self._pending: List[_Packed] = []
+        self._pending_bytes = 0
+        self._pending_by_storage: Dict[tuple, _Packed] = {}
+        self._batches: List[_Batch] = []
+        self._resident: List[_Batch] = []         # swap mode: batches still on the device, oldest first
+        self._resident_sum = 0
+        self._descs = (TensorDesc * _MAX_BATCH)()
+        self._ws: Optional[torch.Tensor] = None
         # swap-out and swap-in each on a stream of their own (Sec. 5.3), both at default priority
         self._out_stream = torch.cuda.Stream() if swap else None
         self._in_stream = torch.cuda.Stream() if swap else None
-        # pinned host memory for the swapped tensors: one arena, handed out front to back within
-        # an iteration (a pinned allocation per tensor costs more than the copy it serves)
+        # pinned host memory for the swapped batches: one arena, handed out front to back within
+        # an iteration (a pinned allocation per copy costs more than the copy it serves)
         self._arena: Optional[torch.Tensor] = None
         self._arena_used = 0
 
@@ -73,143 +125,261 @@ class Controller:
         # The arena is reused from its start: the copies that read it in the last backward
         # pass were waited for by the main stream, which orders them before this iteration's
         # swap-outs (those wait for an event the main stream records after compressing).
+        if not self._frozen:
+            self.iteration += 1
+            self._iter_key = _mix64(self.base_seed ^ _mix64(self.iteration))
         self._arena_used = 0
-        self._index = 0
-        self._live.clear()
-        self._by_storage.clear()
+        self._handles = []
+        self._pending = []
+        self._pending_bytes = 0
+        self._pending_by_storage = {}
+        self._batches = []
+        self._resident = []
+        self._resident_sum = 0
         self.numel = []
 
+    def set_iteration(self, k: int) -> None:
+        """The next ``begin_iteration`` starts iteration k: replays that iteration's seeds."""
+        self.iteration = k - 1
+
     def seed_of(self, index: int) -> int:
-        return self.seed_override.get(index, self.base_seed * 1_000_003 + index)
+        """r_l of context tensor `index` in the current iteration."""
+        s = self.seed_override.get(index)
+        return s if s is not None else (self._iter_key + index * 0x9E3779B97F4A7C15) & _MASK64
 
     def bits_of(self, index: int) -> int:
         return self.bits.get(index, self.default_bits)
 
     def _eligible(self, x: torch.Tensor) -> bool:
-        return (x.is_cuda and x.dtype in (torch.float32, torch.bfloat16) and x.numel() >= self.min_numel
+        return (x.is_cuda and x.requires_grad and x.numel() >= self.min_numel
+                and x.dtype in (torch.float32, torch.bfloat16)
                 and x.data_ptr() not in self.param_ptrs and x.is_contiguous())
 
     # ------------------------------------------------------------------ hooks
     def pack(self, x: torch.Tensor):
         if not self._eligible(x):
             return x
-        index = self._index
-        b = self.bits_of(index)
-        if b == GACT_BITS_UNCOMPRESSED:
-            self._index += 1
-            self.numel.append(x.numel())
-            return x
-        blob, out = None, (None, None, None)
-        if self.swap:
-            # packed codes, minima and steps in one buffer, so that a swap is one copy each way
-            blob = torch.empty(self._blob_bytes(x.numel(), b), dtype=torch.uint8, device=x.device)
-            out = self._views(blob, x.numel(), b)
         if self.dedup:
-            # one read: the sum is taken in the compressor's statistics pass
-            packed, gmin, gscale, fp = gact_compress_footprint(x.detach(), self.group_size, b,
-                                                               self.seed_of(index), 8, *out)
             key = (x.data_ptr(), x.numel(), x.dtype)
-            hit = self._by_storage.get(key)
-            if hit is not None and torch.equal(fp, hit[1]):
-                return hit[0]                        # saved before in this iteration: share it, drop the new copy
-        else:
-            packed, gmin, gscale = gact_compress(x.detach(), self.group_size, b, self.seed_of(index), *out)
-        self._index += 1
-        self.numel.append(x.numel())
-        h = _Packed(index, x.shape, x.dtype, x.numel(), b, packed, gmin, gscale, blob)
-        if self.swap:
-            self._swap_out(h)
-        self._live[index] = h
+            hit = self._pending_by_storage.get(key)
+            if hit is not None and hit.x is not None and hit.version == x._version and hit.shape == x.shape:
+                return hit                           # saved before, still held: share it
+        index = len(self._handles)
+        n = x.numel()
+        b = self.bits_of(index)
+        self.numel.append(n)
+        if b == GACT_BITS_UNCOMPRESSED:
+            self._handles.append(None)
+            return x
+        h = _Packed(index, x.shape, x.dtype, n, b, self.seed_of(index), x.detach())
+        self._handles.append(h)
+        self._pending.append(h)
+        self._pending_bytes += n * x.element_size()
         if self.dedup:
-            self._by_storage[key] = (h, fp)
+            self._pending_by_storage[key] = h
+        if len(self._pending) >= self.batch_tensors or self._pending_bytes >= self.batch_bytes:
+            self._flush()
         return h
 
     def unpack(self, h):
         if not isinstance(h, _Packed):
             return h
-        if h.host is not None:
-            self._swap_in(h)
-            nxt = self._live.get(h.index - 1)          # backward walks the tensors in reverse
-            if nxt is not None and nxt.host is not None and nxt.packed is None:
-                self._start_swap_in(nxt)
-            torch.cuda.current_stream().wait_event(h.in_event)
-        y = gact_decompress(h.packed, h.gmin, h.gscale, h.n, self.group_size, h.bits, dtype=h.dtype)
+        if h.batch is None:
+            self._flush()                            # the backward pass has begun
+        if h.y is None:
+            self._decompress_ahead(h)
+        y, h.y, h.done = h.y, None, True
         return y.view(h.shape)
 
     def hooks(self):
         """Context manager: ``with controller.hooks(): loss = model(x)``."""
         return torch.autograd.graph.saved_tensors_hooks(self.pack, self.unpack)
 
+    # ------------------------------------------------------------ compression
+    def _workspace(self, device) -> torch.Tensor:
+        if self._ws is None or self._ws.device != device:
+            self._ws = torch.empty(gact_multi_workspace_bytes(_MAX_BATCH), dtype=torch.uint8, device=device)
+        return self._ws
+
+    def _flush(self) -> None:
+        """One gact_compress_multi launch over the pending tensors, into one buffer."""
+        pend = self._pending
+        if not pend:
+            return
+        G = self.group_size
+        total = 0
+        for h in pend:
+            if h.x._version != h.version:
+                raise RuntimeError("a tensor saved for backward was modified in place before it was compressed")
+            pb = gact_packed_bytes(h.n, h.bits)
+            ng4 = 4 * gact_num_groups(h.n, G)
+            mb = (ng4 + 15) & ~15
+            h.off = (total, total + pb, total + pb + mb)          # all multiples of 16
+            total += pb + 2 * mb
+        dev = pend[0].x.device
+        blob = torch.empty(total, dtype=torch.uint8, device=dev)
+        base = blob.data_ptr()
+        descs = self._descs
+        for k, h in enumerate(pend):
+            d = descs[k]
+            d.x = h.x.data_ptr()
+            d.packed, d.gmin, d.gscale = base + h.off[0], base + h.off[1], base + h.off[2]
+            d.y = None
+            d.n = h.n
+            d.seed = h.seed
+            d.bits = h.bits
+            d.dtype = dtype_code(h.dtype)
+            d.index_base = 0
+        ws = self._workspace(dev)
+        rc = lib.gact_compress_multi(ctypes.addressof(descs), len(pend), G, ws.data_ptr(), ws.numel(),
+                                     torch.cuda.current_stream().cuda_stream)
+        if rc != GACT_OK:
+            raise GactError(rc, "gact_compress_multi")
+        batch = _Batch(len(pend), blob)
+        for h in pend:
+            h.batch = batch
+            h.x = None                                # the uncompressed tensor may go now
+        self._batches.append(batch)
+        self._pending = []
+        self._pending_bytes = 0
+        self._pending_by_storage = {}
+        if self.swap:
+            self._resident.append(batch)
+            self._resident_sum += batch.nbytes
+            while self._resident and self._resident_sum > self.resident_bytes:
+                old = self._resident.pop(0)
+                self._resident_sum -= old.nbytes
+                self._swap_out(old)
+
+    def _decompress_ahead(self, h: _Packed) -> None:
+        """One gact_decompress_multi launch for `h` and the tensors the backward pass will ask for
+        next (those packed just before it), within the look-ahead limits."""
+        todo, nbytes = [h], h.n * (2 if h.dtype == torch.bfloat16 else 4)
+        k = h.index - 1
+        while k >= 0 and len(todo) < self.ahead_tensors:
+            g = self._handles[k]
+            k -= 1
+            if g is None or g.done or g.y is not None or g.batch is None:
+                continue
+            size = g.n * (2 if g.dtype == torch.bfloat16 else 4)
+            if nbytes + size > self.ahead_bytes:
+                break
+            if self.swap and g.batch is not h.batch and g.batch.blob is None:
+                self._start_swap_in(g.batch)         # prefetch its batch; decompress it on a later call
+                break
+            todo.append(g)
+            nbytes += size
+        if self.swap:
+            self._ensure_on_device(h.batch)
+        main = torch.cuda.current_stream()
+        descs = self._descs
+        dev = h.batch.blob.device
+        for j, g in enumerate(todo):
+            if g.batch.in_event is not None:
+                main.wait_event(g.batch.in_event)
+            g.y = torch.empty(g.n, dtype=g.dtype, device=dev)
+            base = g.batch.blob.data_ptr()
+            d = descs[j]
+            d.x = None
+            d.packed, d.gmin, d.gscale = base + g.off[0], base + g.off[1], base + g.off[2]
+            d.y = g.y.data_ptr()
+            d.n = g.n
+            d.seed = 0
+            d.bits = g.bits
+            d.dtype = dtype_code(g.dtype)
+            d.index_base = 0
+            g.batch.remaining -= 1
+        ws = self._workspace(dev)
+        rc = lib.gact_decompress_multi(ctypes.addressof(descs), len(todo), self.group_size, ws.data_ptr(),
+                                       ws.numel(), main.cuda_stream)
+        if rc != GACT_OK:
+            raise GactError(rc, "gact_decompress_multi")
+        if self.swap:
+            # prefetch the batch packed before this one while its successor is being used
+            i = self._batches.index(h.batch)
+            if i > 0 and self._batches[i - 1].blob is None:
+                self._start_swap_in(self._batches[i - 1])
+            # a swapped batch leaves the device again once all its tensors have been handed back
+            # (the launch above is ordered before the release; a second unpack fetches it again)
+            for g in todo:
+                b = g.batch
+                if b.remaining <= 0 and b.host is not None and b.blob is not None:
+                    b.blob, b.in_event, b.remaining = None, None, b.count
+
     # ------------------------------------------------------------------- swap
-    def _pinned(self, like: torch.Tensor) -> torch.Tensor:
-        """A pinned host buffer shaped like `like`, cut from the arena."""
-        nbytes = like.numel() * like.element_size()
+    def _pinned(self, nbytes: int) -> torch.Tensor:
+        """A pinned host buffer of nbytes, cut from the arena."""
         start = (self._arena_used + 255) & ~255
         if self._arena is None or start + nbytes > self._arena.numel():
-            # grow: handles of this iteration keep the old arena's storage alive through their views
+            # grow: batches of this iteration keep the old arena's storage alive through their views
             grown = max(2 * (self._arena.numel() if self._arena is not None else 0), nbytes, 64 << 20)
             self._arena = torch.empty(grown, dtype=torch.uint8, pin_memory=True)
             start = 0
         self._arena_used = start + nbytes
-        return self._arena[start:start + nbytes].view(like.dtype).view(like.shape)
+        return self._arena[start:start + nbytes]
 
-    def _blob_bytes(self, n: int, bits: int) -> int:
-        return gact_packed_bytes(n, bits) + 8 * gact_num_groups(n, self.group_size)
-
-    def _views(self, blob: torch.Tensor, n: int, bits: int):
-        """(packed, gmin, gscale) inside `blob`; the packed size is a multiple of 16 bytes."""
-        pb, ng = gact_packed_bytes(n, bits), gact_num_groups(n, self.group_size)
-        return (blob[:pb], blob[pb:pb + 4 * ng].view(torch.float32),
-                blob[pb + 4 * ng:pb + 8 * ng].view(torch.float32))
-
-    def _swap_out(self, h: _Packed) -> None:
+    def _swap_out(self, batch: _Batch) -> None:
         done = torch.cuda.Event()
-        done.record()                                   # compression finished on the main stream
-        buf = self._pinned(h.blob)
+        done.record()                                   # its compression is enqueued on the main stream
+        buf = self._pinned(batch.nbytes)
         with torch.cuda.stream(self._out_stream):
             self._out_stream.wait_event(done)
-            buf.copy_(h.blob, non_blocking=True)
-            h.blob.record_stream(self._out_stream)
-            h.out_event = torch.cuda.Event()
-            h.out_event.record()
-        h.host = buf
-        h.blob = h.packed = h.gmin = h.gscale = None    # the device copy may be reused once copied
+            buf.copy_(batch.blob, non_blocking=True)
+            batch.blob.record_stream(self._out_stream)
+            batch.out_event = torch.cuda.Event()
+            batch.out_event.record()
+        batch.host = buf
+        batch.blob = None                               # the device copy may be reused once copied
 
-    def _start_swap_in(self, h: _Packed) -> None:
+    def _start_swap_in(self, batch: _Batch) -> None:
+        if batch.blob is not None or batch.host is None:
+            return
+        # The buffer comes from the main stream's pool (a buffer allocated under the side stream would
+        # be handed back to that stream's pool only after cross-stream bookkeeping, and the next
+        # iteration would find the pool empty and go to the driver).  Its memory may still be in use
+        # by work already enqueued on the main stream, so the copy waits for that point.
         main = torch.cuda.current_stream()
+        blob = torch.empty(batch.nbytes, dtype=torch.uint8, device="cuda")
+        here = torch.cuda.Event()
+        here.record(main)
         with torch.cuda.stream(self._in_stream):
-            self._in_stream.wait_event(h.out_event)
-            blob = torch.empty(h.host.shape, dtype=torch.uint8, device="cuda")
-            blob.copy_(h.host, non_blocking=True)
-            blob.record_stream(main)
-            h.in_event = torch.cuda.Event()
-            h.in_event.record()
-        h.blob = blob
-        h.packed, h.gmin, h.gscale = self._views(blob, h.n, h.bits)
+            self._in_stream.wait_event(here)
+            self._in_stream.wait_event(batch.out_event)
+            blob.copy_(batch.host, non_blocking=True)
+            blob.record_stream(self._in_stream)
+            batch.in_event = torch.cuda.Event()
+            batch.in_event.record()
+        batch.blob = blob
 
-    def _swap_in(self, h: _Packed) -> None:
-        if h.packed is None:
-            self._start_swap_in(h)
+    def _ensure_on_device(self, batch: _Batch) -> None:
+        if batch.blob is None:
+            self._start_swap_in(batch)
 
     # ------------------------------------------------------------ adaptation
     def compute_sensitivities(self, fwdbwd: Callable[[], Sequence[torch.Tensor]]) -> np.ndarray:
         """Alg. 1 for every context tensor.  ``fwdbwd`` runs one forward and
         backward pass under ``self.hooks()`` on a fixed batch and returns the
         gradient buffers.  L + 1 passes: one with the seeds (r_l), then one per
-        tensor with only that tensor's seed replaced by r_{L+1}."""
+        tensor with only that tensor's seed replaced by r_{L+1}.  All passes use
+        the seeds of one iteration: the iteration counter does not advance here."""
         self.seed_override.clear()
         self.begin_iteration()
-        g0 = [g.detach().clone() for g in fwdbwd()]
-        L = len(self.numel)
-        c = np.zeros(L, dtype=np.float32)
-        for l in range(L):
-            if self.bits_of(l) == GACT_BITS_UNCOMPRESSED:
-                continue
-            self.seed_override = {l: self.base_seed * 1_000_003 + L + 1_000_000}
-            self.begin_iteration()
-            g1 = fwdbwd()
-            c[l] = float(gact_sensitivity(g0, [g.detach() for g in g1], self.bits_of(l)).item())
-        self.seed_override.clear()
+        self._frozen = True
+        try:
+            g0 = [g.detach().clone() for g in fwdbwd()]
+            L = len(self.numel)
+            c = np.zeros(L, dtype=np.float32)
+            other = (self._iter_key + (L + 1_000_000) * 0x9E3779B97F4A7C15) & _MASK64      # r_{L+1}
+            for l in range(L):
+                if self.bits_of(l) == GACT_BITS_UNCOMPRESSED:
+                    continue
+                self.seed_override = {l: other}
+                self.begin_iteration()
+                g1 = fwdbwd()
+                c[l] = float(gact_sensitivity(g0, [g.detach() for g in g1], self.bits_of(l)).item())
+        finally:
+            self._frozen = False
+            self.seed_override.clear()
         self.sensitivity = c
         return c
 
