@@ -97,12 +97,21 @@ constexpr int64_t reduce_chunk_elems(int dtype) { return dtype == GACT_DT_F32 ? 
 
 // Decompress launch shape.  A unit is the 1 KB of output one coalesced
 // wavefront store covers (256 fp32 or 512 bf16 elements); a block of four
-// wavefronts takes 4 * units consecutive units.  Units per wavefront were
-// chosen by sweep on MI355X over the benchmark activation sets (% of HBM peak,
-// decompress): fp32 1/2/3/4/8 units -> 52/66/72/75/65, bf16 1/2/3/4 units ->
-// 60/79/69/70 (BERT-shaped) and 56/73/72/73 (ViT-shaped).
-constexpr int dec_units_per_wave(int dtype, int /*bits*/) {
-    return dtype == GACT_DT_F32 ? 4 : 2;
+// wavefronts takes 4 * units consecutive units.  Units per wavefront trade the
+// load latency a wavefront hides against the length of its store burst; the
+// best value depends on dtype and code width and was chosen by sweep on MI355X
+// (% of HBM peak, decompress, 32 tensors of 13 / 26 M elements):
+//            units  1     2     3     4     6
+//   bf16 b=1      59.4  66.9  71.7  65.8  64.0
+//   bf16 b=2      61.2  75.2  74.7  75.4  68.0   (2 units: 68.8 in a second run)
+//   bf16 b=4      63.3  79.5  76.2  72.8  74.1
+//   bf16 b=8      72.8  80.6  74.3  75.4  75.0
+//   fp32 b=1      56.8  75.0  78.8  73.6  66.1
+//   fp32 b=2      56.9  68.4  76.9  77.1  62.2
+//   fp32 b=4      57.5  75.8  72.2  69.6  63.5
+//   fp32 b=8      63.9  79.2  66.2  66.7  62.6
+constexpr int dec_units_per_wave(int /*dtype*/, int bits) {
+    return bits == 1 ? 3 : bits == 2 ? 4 : 2;
 }
 constexpr int dec_block_elems(int dtype, int bits) {
     return 4 * dec_units_per_wave(dtype, bits) * (dtype == GACT_DT_F32 ? 256 : 512);
