@@ -50,9 +50,8 @@ HBM_PEAK_GBPS = 8000.0       # MI355X HBM3E, published
 # published 157.3 TFLOP/s of fp32 vector FMA.  Multiplies, conversions and three-operand integer
 # instructions issue at half of it.
 VALU_PEAK_LANE_OPS = 256 * 128 * 2.4e9
-# VALU instructions per element of the compress kernel: instructions of one full tile in the
-# kernel's code (bf16 / fp32, 4-bit codes) over its 2048 elements x 64 lanes
-COMPRESS_VALU_PER_ELEMENT = {"f32": 16.7, "bf16": 17.3}
+# VALU instructions per element of the compress kernel, from SQ_INSTS_VALU x 64 / elements (profiles/)
+COMPRESS_VALU_PER_ELEMENT = {"f32": 14.9, "bf16": 15.7}
 
 WORKLOADS = {
     # name: (set builder, group size, average bits, sensitivity seed, uniform bits, description)
