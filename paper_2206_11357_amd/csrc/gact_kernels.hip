@@ -72,10 +72,14 @@ __device__ __forceinline__ float fmax2(float a, float b) { return __builtin_fmax
 // v = min / max(v, v of the DPP-selected lane) in one instruction.  Written as
 // assembly because the compiler otherwise moves the DPP operand into its own
 // register and re-canonicalises both inputs (4 instructions per step).
+// A DPP operand must not be read in the two issue slots after a vector
+// instruction has written it, and the compiler's hazard pass does not look
+// inside an assembly statement, so each statement brings its own wait states.
 #define GACT_DPP_MINMAX(NAME, OP, CTRL)                                                  \
     __device__ __forceinline__ float NAME(float v) {                                     \
         float r;                                                                          \
-        asm(OP " %0, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf" : "=v"(r) : "v"(v));  \
+        asm("s_nop 1\n\t" OP " %0, %1, %1 " CTRL " row_mask:0xf bank_mask:0xf"          \
+            : "=v"(r) : "v"(v));                                                          \
         return r;                                                                         \
     }
 GACT_DPP_MINMAX(min_xor1, "v_min_f32_dpp", "quad_perm:[1,0,3,2]")
