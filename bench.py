@@ -179,6 +179,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD,
                     choices=sorted(WORKLOADS) + ["grad_sensitivity", "single_1m", "hooks_transformer", "fused_footprint"])
+    ap.add_argument("--swap-workgroups", type=int, default=16,
+                    help="hooks_transformer: workgroups of the kernel that copies compressed batches to the host")
+    ap.add_argument("--prefetch-batches", type=int, default=8,
+                    help="hooks_transformer: swapped batches fetched ahead of use in the backward pass")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-config", action="store_true", help="skip the other benchmark sets")
     ap.add_argument("--cpu-sample-elems", type=int, default=1_400_000_000)
@@ -659,6 +663,8 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
         for _ in range(warmup):
             one()
         torch.cuda.synchronize()
+        if ctl is not None:
+            ctl.release()                    # the last warm-up step's compressed buffers are not part of the base
         torch.cuda.reset_peak_memory_stats()
         base = torch.cuda.memory_allocated()
         t0 = time.perf_counter()
@@ -667,16 +673,25 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps
         return {"ms_per_step": round(dt * 1e3, 2), "loss": round(float(loss.detach()), 5),
-                "peak_activation_MB": round((torch.cuda.max_memory_allocated() - base) / 2**20, 1)}
+                "peak_activation_MB": round((torch.cuda.max_memory_allocated() - base) / 2**20, 1),
+                "compressed_MB": None if ctl is None else round(sum(b.nbytes for b in ctl._batches) / 2**20, 1),
+                "swapped_MB": None if ctl is None else round(sum(b.nbytes for b in ctl._batches if b.host is not None) / 2**20, 1)}
 
-    steps, warmup = max(args.steps // 4, 3), 2
+    steps, warmup = max(args.steps // 4, 3), max(args.warmup, 2)
     params = list(model.parameters())
     res = {"no_hooks": run(None, steps, warmup)}
-    res["compress_4bit"] = run(Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14), steps, warmup)
-    res["compress_2bit"] = run(Controller(params, group_size=256, bits=2, seed=0, min_numel=1 << 14), steps, warmup)
-    res["compress_4bit_swap"] = run(Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14, swap=True), steps, warmup)
-    res["compress_4bit_swap_resident_256MB"] = run(Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14,
-                                                              swap=True, resident_bytes=256 << 20), steps, warmup)
+    wg, pf = args.swap_workgroups, args.prefetch_batches
+
+    def level(bits, **kw):
+        return run(Controller(params, group_size=256, bits=bits, seed=0, min_numel=1 << 14, swap_workgroups=wg,
+                              prefetch_batches=pf, **kw), steps, warmup)
+    res["compress_4bit_no_dedup"] = level(4)
+    res["compress_4bit"] = level(4, dedup=True)
+    res["compress_2bit"] = level(2, dedup=True)
+    res["compress_4bit_swap"] = level(4, dedup=True, swap=True)
+    res["compress_4bit_swap_limit_384MB"] = level(4, dedup=True, swap=True, swap_limit_bytes=384 << 20)
+    res["compress_2bit_swap"] = level(2, dedup=True, swap=True)
+    res["compress_2bit_swap_limit_192MB"] = level(2, dedup=True, swap=True, swap_limit_bytes=192 << 20)
     ref = res["no_hooks"]
     for k, r in res.items():
         r["activation_memory_ratio"] = round(ref["peak_activation_MB"] / max(r["peak_activation_MB"], 1e-9), 2)
@@ -687,7 +702,7 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
         "warmup": warmup, "ms_per_step": res["compress_4bit"]["ms_per_step"], "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "hooks_transformer", "layers": layers, "hidden": H, "heads": heads, "ffn": F,
-                   "batch": B, "seq_len": S, "group_size": 256,
+                   "batch": B, "seq_len": S, "group_size": 256, "swap_workgroups": wg, "prefetch_batches": pf,
                    "description": "pre-LN encoder with explicit softmax attention, SGD, MSE loss on random data; "
                                   "peak memory above what is allocated before the step"},
         "levels": res,

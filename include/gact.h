@@ -245,6 +245,19 @@ int gact_compress_footprint(const void *d_x, gact_dtype dtype, int64_t n, int gr
                             void *d_workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * Copy of nbytes between buffers a kernel can address -- device memory, or host
+ * memory that is pinned and mapped (hipHostMalloc) -- by a kernel of
+ * `workgroups` workgroups (1..1024), enqueued on `stream`.  For the swap of
+ * compressed activations to the host that Sec. 5.3 runs on a stream of its own
+ * next to the forward pass: a few workgroups keep PCIe busy and leave the rest
+ * of the GPU to the model, which the runtime's own device-to-host copy kernel
+ * does not.  dst and src 16-byte aligned and not overlapping.  A pointer that
+ * no kernel may touch (ordinary host memory) returns GACT_E_ARG, nothing is
+ * enqueued.
+ */
+int gact_copy_bounded(void *dst, const void *src, size_t nbytes, int workgroups, void *stream);
+
+/*
  * gact_compress_footprint for callers that cannot allocate device memory and
  * so cannot bring a workspace: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  The per-tile partial sums go to a

@@ -36,7 +36,7 @@ EXPORTS = (
     "gact_decompress_multi", "gact_allocate_bits", "gact_reduce_workspace_bytes",
     "gact_sensitivity", "gact_grad_stats_update", "gact_variance_alert",
     "gact_allocate_bits_levels", "gact_footprint", "gact_compress_footprint",
-    "gact_compress_footprint_workspace_bytes", "gact_compress_footprint_noalloc",
+    "gact_compress_footprint_workspace_bytes", "gact_compress_footprint_noalloc", "gact_copy_bounded",
 )
 GACT_BITS_UNCOMPRESSED = 32
 
@@ -109,6 +109,8 @@ def _load() -> ctypes.CDLL:
     lib.gact_compress_footprint.restype = i32
     lib.gact_compress_footprint_noalloc.argtypes = [vp, i32, i64, i32, i32, ctypes.c_uint64, vp, vp, vp, i32, vp, vp]
     lib.gact_compress_footprint_noalloc.restype = i32
+    lib.gact_copy_bounded.argtypes = [vp, vp, sz, i32, vp]
+    lib.gact_copy_bounded.restype = i32
     lib.gact_variance_alert.argtypes = [vp, vp, i32, ctypes.c_double, ctypes.c_double, vp]
     lib.gact_variance_alert.restype = i32
     return lib
@@ -436,6 +438,16 @@ def gact_compress_footprint_noalloc(x: torch.Tensor, group_size: int, bits: int,
                                              _stream(stream))
     if rc != GACT_OK:
         raise GactError(rc, "gact_compress_footprint_noalloc")
+
+
+def gact_copy_bounded(dst: torch.Tensor, src: torch.Tensor, workgroups: int = 16, stream=None) -> None:
+    """dst <- src (same byte size; device tensors or pinned host tensors) by a kernel of `workgroups` workgroups."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src differ in size")
+    rc = lib.gact_copy_bounded(dst.data_ptr(), src.data_ptr(), nbytes, workgroups, _stream(stream))
+    if rc != GACT_OK:
+        raise GactError(rc, "gact_copy_bounded")
 
 
 def gact_variance_alert(sensitivity, bits, grad_var: float, threshold: float):

@@ -9,6 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgact.so")
 SOURCES = [os.path.join(CSRC, "gact_kernels.hip"), os.path.join(CSRC, "gact_reduce.hip"),
+           os.path.join(CSRC, "gact_copy.hip"),
            os.path.join(CSRC, "gact_api.cpp"), os.path.join(CSRC, "gact_host.cpp")]
 
 # standalone measurement tool, not part of the library

@@ -423,6 +423,27 @@ int gact_compress_footprint(const void* d_x, gact_dtype dtype, int64_t n, int gr
                               n_samples, d_footprint, d_workspace, workspace_bytes, false, stream);
 }
 
+// The address a kernel can use for `p`: device memory as it is; host memory only when it is pinned
+// and mapped into the device's address space.  nullptr when a kernel must not touch it.
+static void* device_visible(const void* p) {
+    hipPointerAttribute_t attr;
+    if (hipPointerGetAttributes(&attr, p) != hipSuccess) {
+        (void)hipGetLastError();                      // an ordinary host pointer: not an error state to keep
+        return nullptr;
+    }
+    return attr.devicePointer;
+}
+
+int gact_copy_bounded(void* dst, const void* src, size_t nbytes, int workgroups, void* stream) {
+    if (workgroups < 1 || workgroups > 1024 || (nbytes > 0 && (!dst || !src))) return GACT_E_ARG;
+    if (nbytes == 0) return GACT_OK;
+    if (!aligned(dst, 16) || !aligned(src, 16)) return GACT_E_ARG;
+    void* d = device_visible(dst);
+    const void* s = device_visible(src);
+    if (!d || !s) return GACT_E_ARG;
+    return gact_launch_copy(d, s, (uint64_t)nbytes, (unsigned)workgroups, stream) == 0 ? GACT_OK : GACT_E_HIP;
+}
+
 int gact_compress_footprint_noalloc(const void* d_x, gact_dtype dtype, int64_t n, int group_size,
                                     int bits, uint64_t seed, void* d_packed, float* d_gmin,
                                     float* d_gscale, int n_samples, double* d_footprint,

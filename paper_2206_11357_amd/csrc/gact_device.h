@@ -134,6 +134,7 @@ extern "C" int gact_launch_zero(double* d_out, int nout, void* stream);
 extern "C" int gact_launch_grad_stats(const gact::ReduceArgs* d_table, const uint32_t* d_first, int K,
                                       float rt, unsigned blocks, double* d_partial, double* d_out,
                                       void* stream);
+extern "C" int gact_launch_copy(void* dst, const void* src, uint64_t nbytes, unsigned workgroups, void* stream);
 extern "C" int gact_launch_multi_inline(int compress, const gact::InlineTable* tab,
                                         const gact::Geometry* geo, unsigned blocks, void* stream);
 extern "C" int gact_launch_multi(int compress, const gact::TensorArgs* d_table,

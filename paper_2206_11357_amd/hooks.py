@@ -21,8 +21,10 @@ from typing import Callable, Dict, List, Optional, Sequence
 
 import numpy as np
 import torch
+from torch.multiprocessing.reductions import StorageWeakRef
 
 from . import (GACT_BITS_UNCOMPRESSED, GACT_OK, GactError, TensorDesc, dtype_code, gact_allocate_bits_levels,
+               gact_copy_bounded,
                gact_multi_workspace_bytes, gact_num_groups, gact_packed_bytes, gact_sensitivity, lib)
 
 _MASK64 = (1 << 64) - 1
@@ -39,7 +41,8 @@ def _mix64(z: int) -> int:
 
 class _Packed:
     """What autograd holds instead of a saved tensor."""
-    __slots__ = ("index", "shape", "dtype", "n", "bits", "seed", "x", "version", "batch", "off", "y", "done")
+    __slots__ = ("index", "shape", "dtype", "n", "bits", "seed", "x", "version", "batch", "off", "y", "done",
+                 "uses", "left")
 
     def __init__(self, index, shape, dtype, n, bits, seed, x):
         self.index, self.shape, self.dtype, self.n, self.bits, self.seed = index, shape, dtype, n, bits, seed
@@ -49,6 +52,17 @@ class _Packed:
         self.off = None            # (packed, gmin, gscale) byte offsets inside the batch's buffer
         self.y = None              # decompressed ahead of use
         self.done = False          # handed back to autograd at least once
+        self.uses = 1              # operators that saved this tensor (more than one when shared)
+        self.left = 0              # of those, how many have yet to ask for the current `y`
+
+
+class _Alias:
+    """A second save of a tensor already held, under another shape (the softmax output that the
+    attention product saves again as a batch of matrices): the same compressed data, viewed anew."""
+    __slots__ = ("base", "shape")
+
+    def __init__(self, base, shape):
+        self.base, self.shape = base, shape
 
 
 class _Batch:
@@ -73,26 +87,40 @@ class Controller:
     ahead_tensors / ahead_bytes   the backward pass decompresses up to this much ahead of use
     swap, resident_bytes          swap compressed batches to pinned host memory, except the most recent
                                   `resident_bytes` of them, which the backward pass needs first
+    swap_workgroups               size of the kernel that copies a batch to the host
+    prefetch_batches              swapped batches fetched ahead of the one the backward pass is using
+    swap_limit_bytes              None: every batch beyond `resident_bytes` is swapped.  A number: at most this
+                                  many bytes per iteration, oldest batches first (the ones the backward pass
+                                  needs last).  The first batch the backward pass needs from the host is
+                                  the last one sent, so it waits until all swap-outs are through: a volume
+                                  that PCIe carries within the forward pass costs no waiting, more does
     """
 
     def __init__(self, params: Sequence[torch.Tensor] = (), group_size: int = 256, bits: int = 4,
                  seed: int = 0, min_numel: int = 1024, swap: bool = False, dedup: bool = False,
                  batch_tensors: int = 32, batch_bytes: int = 128 << 20, ahead_tensors: int = 32,
-                 ahead_bytes: int = 128 << 20, resident_bytes: int = 0):
+                 ahead_bytes: int = 128 << 20, resident_bytes: int = 0, swap_workgroups: int = 16,
+                 prefetch_batches: int = 8, swap_limit_bytes: Optional[int] = None):
         self.group_size = group_size
         self.default_bits = bits
         self.base_seed = seed
         self.min_numel = min_numel
         self.swap = swap
         # dedup: a tensor that several operators save (the input shared by the Q, K and V projections)
-        # is compressed once.  While a tensor waits in the current batch the controller holds it, so
-        # "same storage, same version counter" identifies it exactly; no footprint has to be computed.
+        # is compressed once.  A weak reference to the storage of every tensor compressed in this
+        # iteration tells whether that storage has been alive ever since; if so, "same storage, same
+        # start and length, same version counter" identifies the tensor exactly, and no footprint has
+        # to be computed.
         self.dedup = dedup
         self.batch_tensors = max(1, min(batch_tensors, _MAX_BATCH))
         self.batch_bytes = batch_bytes
         self.ahead_tensors = max(1, min(ahead_tensors, _MAX_BATCH))
         self.ahead_bytes = ahead_bytes
         self.resident_bytes = resident_bytes
+        self.swap_workgroups = swap_workgroups
+        self.prefetch_batches = max(1, prefetch_batches)
+        self.swap_limit_bytes = swap_limit_bytes
+        self._swapped_bytes = 0
         self.param_ptrs = {p.data_ptr() for p in params}
         self.bits: Dict[int, int] = {}            # index l -> b_l
         self.seed_override: Dict[int, int] = {}   # index l -> r_l (Alg. 1 reseeds one tensor)
@@ -106,7 +134,7 @@ class Controller:
         self._handles: List[_Packed] = []         # by index, this iteration
         self._pending: List[_Packed] = []
         self._pending_bytes = 0
-        self._pending_by_storage: Dict[tuple, _Packed] = {}
+        self._pending_by_storage: Dict[tuple, tuple] = {}   # (storage weak reference, handle)
         self._batches: List[_Batch] = []
         self._resident: List[_Batch] = []         # swap mode: batches still on the device, oldest first
         self._resident_sum = 0
@@ -128,7 +156,14 @@ class Controller:
         if not self._frozen:
             self.iteration += 1
             self._iter_key = _mix64(self.base_seed ^ _mix64(self.iteration))
+        self.release()
+        self.numel = []
+
+    def release(self) -> None:
+        """Drop the compressed buffers of the last iteration (they are kept after the backward pass so
+        that a second backward pass through a retained graph still finds them)."""
         self._arena_used = 0
+        self._swapped_bytes = 0
         self._handles = []
         self._pending = []
         self._pending_bytes = 0
@@ -136,7 +171,6 @@ class Controller:
         self._batches = []
         self._resident = []
         self._resident_sum = 0
-        self.numel = []
 
     def set_iteration(self, k: int) -> None:
         """The next ``begin_iteration`` starts iteration k: replays that iteration's seeds."""
@@ -161,9 +195,16 @@ class Controller:
             return x
         if self.dedup:
             key = (x.data_ptr(), x.numel(), x.dtype)
-            hit = self._pending_by_storage.get(key)
-            if hit is not None and hit.x is not None and hit.version == x._version and hit.shape == x.shape:
-                return hit                           # saved before, still held: share it
+            storage = x.untyped_storage()
+            held = self._pending_by_storage.get(key)
+            if held is not None:
+                ref, hit = held
+                # Saved before, from a storage that has been alive ever since (so the address was not
+                # handed to another tensor) and with the same version counter (so nothing wrote to it):
+                # the same elements in the same order, both being contiguous, whatever the shapes.
+                if not ref.expired() and ref.cdata == storage._cdata and hit.version == x._version:
+                    hit.uses += 1
+                    return hit if hit.shape == x.shape else _Alias(hit, x.shape)
         index = len(self._handles)
         n = x.numel()
         b = self.bits_of(index)
@@ -176,20 +217,27 @@ class Controller:
         self._pending.append(h)
         self._pending_bytes += n * x.element_size()
         if self.dedup:
-            self._pending_by_storage[key] = h
+            self._pending_by_storage[key] = (StorageWeakRef(storage), h)
         if len(self._pending) >= self.batch_tensors or self._pending_bytes >= self.batch_bytes:
             self._flush()
         return h
 
     def unpack(self, h):
+        shape = None
+        if isinstance(h, _Alias):
+            h, shape = h.base, h.shape
         if not isinstance(h, _Packed):
             return h
         if h.batch is None:
             self._flush()                            # the backward pass has begun
         if h.y is None:
             self._decompress_ahead(h)
-        y, h.y, h.done = h.y, None, True
-        return y.view(h.shape)
+        # one decompression serves every operator that saved the tensor; the last of them takes it away
+        y, h.done = h.y, True
+        h.left -= 1
+        if h.left <= 0:
+            h.y = None
+        return y.view(h.shape if shape is None else shape)
 
     def hooks(self):
         """Context manager: ``with controller.hooks(): loss = model(x)``."""
@@ -242,11 +290,13 @@ class Controller:
         self._batches.append(batch)
         self._pending = []
         self._pending_bytes = 0
-        self._pending_by_storage = {}
         if self.swap:
             self._resident.append(batch)
             self._resident_sum += batch.nbytes
             while self._resident and self._resident_sum > self.resident_bytes:
+                if (self.swap_limit_bytes is not None
+                        and self._swapped_bytes + self._resident[0].nbytes > self.swap_limit_bytes):
+                    break                             # this iteration's share of PCIe is used up
                 old = self._resident.pop(0)
                 self._resident_sum -= old.nbytes
                 self._swap_out(old)
@@ -278,6 +328,7 @@ class Controller:
             if g.batch.in_event is not None:
                 main.wait_event(g.batch.in_event)
             g.y = torch.empty(g.n, dtype=g.dtype, device=dev)
+            g.left = g.uses
             base = g.batch.blob.data_ptr()
             d = descs[j]
             d.x = None
@@ -295,10 +346,11 @@ class Controller:
         if rc != GACT_OK:
             raise GactError(rc, "gact_decompress_multi")
         if self.swap:
-            # prefetch the batch packed before this one while its successor is being used
+            # prefetch the batches packed before this one while it is being used: several, so that the
+            # copies run back to back whether the backward pass dwells on a batch or rushes through it
             i = self._batches.index(h.batch)
-            if i > 0 and self._batches[i - 1].blob is None:
-                self._start_swap_in(self._batches[i - 1])
+            for j in range(i - 1, max(i - 1 - self.prefetch_batches, -1), -1):
+                self._start_swap_in(self._batches[j])
             # a swapped batch leaves the device again once all its tensors have been handed back
             # (the launch above is ordered before the release; a second unpack fetches it again)
             for g in todo:
@@ -324,10 +376,13 @@ class Controller:
         buf = self._pinned(batch.nbytes)
         with torch.cuda.stream(self._out_stream):
             self._out_stream.wait_event(done)
-            buf.copy_(batch.blob, non_blocking=True)
+            # a copy kernel of a few workgroups: it keeps PCIe busy and leaves the wave slots of the
+            # GPU to the forward pass, which the runtime's whole-chip device-to-host copy does not
+            gact_copy_bounded(buf, batch.blob, self.swap_workgroups, self._out_stream)
             batch.blob.record_stream(self._out_stream)
             batch.out_event = torch.cuda.Event()
             batch.out_event.record()
+        self._swapped_bytes += batch.nbytes
         batch.host = buf
         batch.blob = None                               # the device copy may be reused once copied
 

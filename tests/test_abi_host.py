@@ -29,6 +29,18 @@ def test_library_exports_every_declared_symbol():
         assert getattr(lib, name) is not None
 
 
+def test_bounded_copy_rejects_bad_arguments_without_a_launch():
+    lib = gact.lib
+    buf = (ctypes.c_char * 4096)()
+    p16 = (ctypes.addressof(buf) + 15) // 16 * 16
+    assert lib.gact_copy_bounded(p16, p16 + 1024, 0, 16, None) == gact.GACT_OK            # nothing to do
+    assert lib.gact_copy_bounded(p16, p16 + 1024, 64, 0, None) == gact.GACT_E_ARG
+    assert lib.gact_copy_bounded(p16, p16 + 1024, 64, 1025, None) == gact.GACT_E_ARG
+    assert lib.gact_copy_bounded(None, p16, 64, 16, None) == gact.GACT_E_ARG
+    assert lib.gact_copy_bounded(p16 + 8, p16 + 1024, 64, 16, None) == gact.GACT_E_ARG    # misaligned
+    assert lib.gact_copy_bounded(p16, p16 + 1024, 64, 16, None) == gact.GACT_E_ARG        # pageable host memory
+
+
 def test_size_helpers_match_the_oracle():
     for n in (0, 1, 7, 8, 31, 32, 127, 128, 129, 1000, 2048, 1 << 20, (1 << 33) + 5):
         for bits in (1, 2, 4, 8):

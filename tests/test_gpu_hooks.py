@@ -173,6 +173,23 @@ def test_a_tensor_saved_by_several_operators_is_compressed_once(gact):
     assert n_again == n_dedup
     for a, b in zip(g_dedup, g_again):
         assert torch.equal(a, b)
+    # the same tensor saved under two shapes (softmax output, then the batched product's operand)
+    a = torch.randn(4, 8, 64, 64, device="cuda", requires_grad=True)
+    w = torch.randn(4, 8, 64, 16, device="cuda", requires_grad=True)
+
+    def attn(ctrl):
+        a.grad = w.grad = None
+        ctrl.begin_iteration()
+        with ctrl.hooks():
+            out = (torch.softmax(a, dim=-1) @ w).sum()
+        out.backward()
+        return len(ctrl.numel), a.grad.clone(), w.grad.clone()
+    n1, ga1, gw1 = attn(Controller((), bits=8, seed=3, dedup=True))
+    n2, ga2, gw2 = attn(Controller((), bits=8, seed=3, dedup=False))
+    assert n2 - n1 >= 1
+    assert torch.equal(ga1, ga2)                 # the first save has the same seed in both runs
+    assert not torch.equal(gw1, gw2)             # the second save had a seed of its own, now it shares
+    assert (gw1 - gw2).norm() <= 0.02 * gw2.norm()
     # a freed activation's address is reused by the next one: same pointer, different
     # footprint, so it is not taken for a duplicate (the MLP test runs with dedup on too)
     model, (xb, yb) = make_model(), batch()
@@ -234,6 +251,16 @@ def test_swap_with_resident_tail_and_small_batches_gives_identical_gradients(gac
         torch.cuda.synchronize()
         for ga, gb in zip(a, b):
             assert torch.equal(ga, gb)
+    # a cap on the bytes swapped per iteration, three batches fetched ahead
+    for backlog in (0, 40 << 10, 1 << 30):
+        ctrl = Controller(model.parameters(), bits=4, seed=9, swap=True, batch_tensors=1, ahead_tensors=1,
+                          swap_limit_bytes=backlog, prefetch_batches=3)
+        b = grads(model, x, y, ctrl)
+        torch.cuda.synchronize()
+        for ga, gb in zip(a, b):
+            assert torch.equal(ga, gb)
+        swapped = sum(bt.host is not None for bt in ctrl._batches)
+        assert swapped == {0: 0, 40 << 10: 1}.get(backlog, len(ctrl._batches))
 
 
 def test_compressed_buffers_of_an_iteration_are_released_at_the_next(gact):

@@ -546,3 +546,25 @@ def test_prepared_calls_give_the_same_bytes_as_the_plain_calls(gact):
         assert torch.equal(y.view(torch.int16), y_ref.view(torch.int16))
     p_ref, mn_ref, sc_ref = oracle.compress(x_np, G, bits, seed)
     assert np.array_equal(to_host(bufs[0]), p_ref)
+
+
+def test_bounded_copy_moves_every_byte_both_ways_and_refuses_pageable_memory(gact):
+    """The swap copy of Sec. 5.3: device to pinned host memory and back, sizes with and without a
+    16-byte tail, few and many workgroups; ordinary host memory is refused before any launch."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev).manual_seed(5)
+    for nbytes, wg in ((16, 1), (4096 + 7, 3), (1 << 20, 16), ((5 << 20) + 13, 16), ((3 << 20) + 16, 1024)):
+        src = torch.randint(0, 256, (nbytes,), dtype=torch.uint8, device=dev, generator=g)
+        host = torch.zeros(nbytes + 32, dtype=torch.uint8, pin_memory=True)
+        gact.gact_copy_bounded(host[:nbytes], src, wg)
+        torch.cuda.synchronize()
+        assert torch.equal(host[:nbytes], src.cpu()) and int(host[nbytes:].sum()) == 0
+        back = torch.zeros(nbytes + 32, dtype=torch.uint8, device=dev)
+        gact.gact_copy_bounded(back[:nbytes], host[:nbytes], wg)
+        torch.cuda.synchronize()
+        assert torch.equal(back[:nbytes], src) and int(back[nbytes:].sum()) == 0
+    with pytest.raises(gact.GactError):
+        gact.gact_copy_bounded(torch.empty(1024, dtype=torch.uint8), src[:1024], 16)
+    with pytest.raises(ValueError):
+        gact.gact_copy_bounded(host[:64], src[:128], 16)
+    torch.cuda.synchronize()
