@@ -190,6 +190,11 @@ def test_a_tensor_saved_by_several_operators_is_compressed_once(gact):
     assert torch.equal(ga1, ga2)                 # the first save has the same seed in both runs
     assert not torch.equal(gw1, gw2)             # the second save had a seed of its own, now it shares
     assert (gw1 - gw2).norm() <= 0.02 * gw2.norm()
+    # shared saves and swapping together: the shared tensor's batch may have left the device when its
+    # second consumer asks; one decompression serves both
+    n3, ga3, gw3 = attn(Controller((), bits=8, seed=3, dedup=True, swap=True, batch_tensors=1, ahead_tensors=1))
+    torch.cuda.synchronize()
+    assert n3 == n1 and torch.equal(ga3, ga1) and torch.equal(gw3, gw1)
     # a freed activation's address is reused by the next one: same pointer, different
     # footprint, so it is not taken for a duplicate (the MLP test runs with dedup on too)
     model, (xb, yb) = make_model(), batch()
