@@ -689,6 +689,7 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
     res["compress_4bit"] = level(4, dedup=True)
     res["compress_2bit"] = level(2, dedup=True)
     res["compress_4bit_swap"] = level(4, dedup=True, swap=True)
+    res["compress_4bit_swap_strict"] = level(4, dedup=True, swap=True, keep_until_copied=False)
     res["compress_4bit_swap_limit_384MB"] = level(4, dedup=True, swap=True, swap_limit_bytes=384 << 20)
     res["compress_2bit_swap"] = level(2, dedup=True, swap=True)
     res["compress_2bit_swap_limit_192MB"] = level(2, dedup=True, swap=True, swap_limit_bytes=192 << 20)

@@ -68,10 +68,10 @@ class _Alias:
 class _Batch:
     """Tensors compressed by one launch into one buffer.  Holds no reference to its handles (they
     point here): a cycle would keep the buffer alive until the garbage collector runs."""
-    __slots__ = ("count", "blob", "nbytes", "host", "out_event", "in_event", "remaining")
+    __slots__ = ("index", "count", "blob", "nbytes", "host", "out_event", "in_event", "remaining")
 
-    def __init__(self, count, blob):
-        self.count, self.blob, self.nbytes = count, blob, blob.numel()
+    def __init__(self, index, count, blob):
+        self.index, self.count, self.blob, self.nbytes = index, count, blob, blob.numel()
         self.host = None           # pinned copy once swapped out
         self.out_event = None
         self.in_event = None
@@ -94,13 +94,19 @@ class Controller:
                                   needs last).  The first batch the backward pass needs from the host is
                                   the last one sent, so it waits until all swap-outs are through: a volume
                                   that PCIe carries within the forward pass costs no waiting, more does
+    keep_until_copied             True: a swapped batch's device copy is let go only when its swap-out is seen
+                                  finished; the backward pass uses the most recent batches from the device
+                                  while their swap-outs are still under way (faster, and the peak follows
+                                  what PCIe manages).  False: let go at once; the backward pass waits for
+                                  every swap-out and fetches every batch back (lowest peak)
     """
 
     def __init__(self, params: Sequence[torch.Tensor] = (), group_size: int = 256, bits: int = 4,
                  seed: int = 0, min_numel: int = 1024, swap: bool = False, dedup: bool = False,
                  batch_tensors: int = 32, batch_bytes: int = 128 << 20, ahead_tensors: int = 32,
                  ahead_bytes: int = 128 << 20, resident_bytes: int = 0, swap_workgroups: int = 16,
-                 prefetch_batches: int = 8, swap_limit_bytes: Optional[int] = None):
+                 prefetch_batches: int = 8, swap_limit_bytes: Optional[int] = None,
+                 keep_until_copied: bool = True):
         self.group_size = group_size
         self.default_bits = bits
         self.base_seed = seed
@@ -120,6 +126,7 @@ class Controller:
         self.swap_workgroups = swap_workgroups
         self.prefetch_batches = max(1, prefetch_batches)
         self.swap_limit_bytes = swap_limit_bytes
+        self.keep_until_copied = keep_until_copied
         self._swapped_bytes = 0
         self.param_ptrs = {p.data_ptr() for p in params}
         self.bits: Dict[int, int] = {}            # index l -> b_l
@@ -138,6 +145,7 @@ class Controller:
         self._batches: List[_Batch] = []
         self._resident: List[_Batch] = []         # swap mode: batches still on the device, oldest first
         self._resident_sum = 0
+        self._out_inflight: List[_Batch] = []     # swap mode: swap-out enqueued, device copy still held
         self._descs = (TensorDesc * _MAX_BATCH)()
         self._ws: Optional[torch.Tensor] = None
         # swap-out and swap-in each on a stream of their own (Sec. 5.3), both at default priority
@@ -171,6 +179,7 @@ class Controller:
         self._batches = []
         self._resident = []
         self._resident_sum = 0
+        self._out_inflight = []
 
     def set_iteration(self, k: int) -> None:
         """The next ``begin_iteration`` starts iteration k: replays that iteration's seeds."""
@@ -265,6 +274,8 @@ class Controller:
             h.off = (total, total + pb, total + pb + mb)          # all multiples of 16
             total += pb + 2 * mb
         dev = pend[0].x.device
+        if self.swap:
+            self._reap_out()
         blob = torch.empty(total, dtype=torch.uint8, device=dev)
         base = blob.data_ptr()
         descs = self._descs
@@ -283,7 +294,7 @@ class Controller:
                                      torch.cuda.current_stream().cuda_stream)
         if rc != GACT_OK:
             raise GactError(rc, "gact_compress_multi")
-        batch = _Batch(len(pend), blob)
+        batch = _Batch(len(self._batches), len(pend), blob)
         for h in pend:
             h.batch = batch
             h.x = None                                # the uncompressed tensor may go now
@@ -320,6 +331,7 @@ class Controller:
             todo.append(g)
             nbytes += size
         if self.swap:
+            self._reap_out(keep_from=h.batch.index - self.prefetch_batches)
             self._ensure_on_device(h.batch)
         main = torch.cuda.current_stream()
         descs = self._descs
@@ -348,7 +360,7 @@ class Controller:
         if self.swap:
             # prefetch the batches packed before this one while it is being used: several, so that the
             # copies run back to back whether the backward pass dwells on a batch or rushes through it
-            i = self._batches.index(h.batch)
+            i = h.batch.index
             for j in range(i - 1, max(i - 1 - self.prefetch_batches, -1), -1):
                 self._start_swap_in(self._batches[j])
             # a swapped batch leaves the device again once all its tensors have been handed back
@@ -384,7 +396,23 @@ class Controller:
             batch.out_event.record()
         self._swapped_bytes += batch.nbytes
         batch.host = buf
-        batch.blob = None                               # the device copy may be reused once copied
+        if self.keep_until_copied:
+            self._out_inflight.append(batch)            # the device copy stays until the copy is seen finished
+        else:
+            batch.blob = None                           # the allocator reuses the memory once the copy is through
+
+    def _reap_out(self, keep_from: Optional[int] = None) -> None:
+        """Let go of the device copies of batches whose swap-out has finished.  Until then the memory
+        cannot be reused anyway, so the copy on the device costs nothing, and a batch the backward
+        pass reaches while its swap-out is still under way (the most recent ones: the first it needs
+        are the last that were sent) is used from the device without waiting for PCIe at all.  In the
+        backward pass batches from index `keep_from` on stay for the same reason: they are inside the
+        prefetch window and would be fetched back at once."""
+        q = self._out_inflight
+        while q and q[0].out_event.query():
+            b = q.pop(0)
+            if keep_from is None or b.index < keep_from:
+                b.blob = None
 
     def _start_swap_in(self, batch: _Batch) -> None:
         if batch.blob is not None or batch.host is None:

@@ -250,9 +250,9 @@ def test_swap_with_resident_tail_and_small_batches_gives_identical_gradients(gac
     from paper_2206_11357_amd.hooks import Controller
     model, (x, y) = make_model(), batch()
     a = grads(model, x, y, Controller(model.parameters(), bits=4, seed=9))
-    for resident in (0, 40 << 10, 1 << 30):
+    for resident, keep in ((0, True), (0, False), (40 << 10, True), (40 << 10, False), (1 << 30, True)):
         b = grads(model, x, y, Controller(model.parameters(), bits=4, seed=9, swap=True, batch_tensors=2,
-                                          ahead_tensors=1, resident_bytes=resident))
+                                          ahead_tensors=1, resident_bytes=resident, keep_until_copied=keep))
         torch.cuda.synchronize()
         for ga, gb in zip(a, b):
             assert torch.equal(ga, gb)
