@@ -91,9 +91,8 @@ class Controller:
     prefetch_batches              swapped batches fetched ahead of the one the backward pass is using
     swap_limit_bytes              None: every batch beyond `resident_bytes` is swapped.  A number: at most this
                                   many bytes per iteration, oldest batches first (the ones the backward pass
-                                  needs last).  The first batch the backward pass needs from the host is
-                                  the last one sent, so it waits until all swap-outs are through: a volume
-                                  that PCIe carries within the forward pass costs no waiting, more does
+                                  needs last).  A volume that PCIe carries within the forward pass costs
+                                  little; beyond it the backward pass is fed at the PCIe rate
     keep_until_copied             True: a swapped batch's device copy is let go only when its swap-out is seen
                                   finished; the backward pass uses the most recent batches from the device
                                   while their swap-outs are still under way (faster, and the peak follows
