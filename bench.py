@@ -36,6 +36,7 @@ its input in a cache.
 from __future__ import annotations
 
 import argparse
+import gc
 import json
 import os
 import sys
@@ -683,16 +684,24 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
     wg, pf = args.swap_workgroups, args.prefetch_batches
 
     def level(bits, **kw):
-        return run(Controller(params, group_size=256, bits=bits, seed=0, min_numel=1 << 14, swap_workgroups=wg,
-                              prefetch_batches=pf, **kw), steps, warmup)
+        ctl = Controller(params, group_size=256, bits=bits, seed=0, min_numel=1 << 14, swap_workgroups=wg,
+                         prefetch_batches=pf, **kw)
+        out = run(ctl, steps, warmup)
+        # the next level starts from an empty allocator cache: blocks that a level leaves waiting on its
+        # side streams slowed the levels after it by up to 5 ms per step
+        del ctl
+        gc.collect()
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        return out
     res["compress_4bit_no_dedup"] = level(4)
     res["compress_4bit"] = level(4, dedup=True)
     res["compress_2bit"] = level(2, dedup=True)
     res["compress_4bit_swap"] = level(4, dedup=True, swap=True)
-    res["compress_4bit_swap_strict"] = level(4, dedup=True, swap=True, keep_until_copied=False)
     res["compress_4bit_swap_limit_384MB"] = level(4, dedup=True, swap=True, swap_limit_bytes=384 << 20)
     res["compress_2bit_swap"] = level(2, dedup=True, swap=True)
     res["compress_2bit_swap_limit_192MB"] = level(2, dedup=True, swap=True, swap_limit_bytes=192 << 20)
+    res["compress_4bit_swap_strict"] = level(4, dedup=True, swap=True, keep_until_copied=False)
     ref = res["no_hooks"]
     for k, r in res.items():
         r["activation_memory_ratio"] = round(ref["peak_activation_MB"] / max(r["peak_activation_MB"], 1e-9), 2)

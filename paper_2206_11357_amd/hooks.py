@@ -39,6 +39,19 @@ def _mix64(z: int) -> int:
     return z ^ (z >> 31)
 
 
+_SIDE_STREAMS: Dict[int, tuple] = {}
+
+
+def _side_streams():
+    """The swap-out and swap-in streams of the current device, made once per process: the runtime maps
+    streams onto a few hardware queues in turn, and which queues a controller's streams share with each
+    other and with the compute stream should not depend on how many controllers came before it."""
+    dev = torch.cuda.current_device()
+    if dev not in _SIDE_STREAMS:
+        _SIDE_STREAMS[dev] = (torch.cuda.Stream(), torch.cuda.Stream())
+    return _SIDE_STREAMS[dev]
+
+
 class _Packed:
     """What autograd holds instead of a saved tensor."""
     __slots__ = ("index", "shape", "dtype", "n", "bits", "seed", "x", "version", "batch", "off", "y", "done",
@@ -126,6 +139,7 @@ class Controller:
         self.prefetch_batches = max(1, prefetch_batches)
         self.swap_limit_bytes = swap_limit_bytes
         self.keep_until_copied = keep_until_copied
+        self._in_backward = False
         self._swapped_bytes = 0
         self.param_ptrs = {p.data_ptr() for p in params}
         self.bits: Dict[int, int] = {}            # index l -> b_l
@@ -148,8 +162,7 @@ class Controller:
         self._descs = (TensorDesc * _MAX_BATCH)()
         self._ws: Optional[torch.Tensor] = None
         # swap-out and swap-in each on a stream of their own (Sec. 5.3), both at default priority
-        self._out_stream = torch.cuda.Stream() if swap else None
-        self._in_stream = torch.cuda.Stream() if swap else None
+        self._out_stream, self._in_stream = _side_streams() if swap else (None, None)
         # pinned host memory for the swapped batches: one arena, handed out front to back within
         # an iteration (a pinned allocation per copy costs more than the copy it serves)
         self._arena: Optional[torch.Tensor] = None
@@ -179,6 +192,7 @@ class Controller:
         self._resident = []
         self._resident_sum = 0
         self._out_inflight = []
+        self._in_backward = False
 
     def set_iteration(self, k: int) -> None:
         """The next ``begin_iteration`` starts iteration k: replays that iteration's seeds."""
@@ -236,6 +250,7 @@ class Controller:
             h, shape = h.base, h.shape
         if not isinstance(h, _Packed):
             return h
+        self._in_backward = True
         if h.batch is None:
             self._flush()                            # the backward pass has begun
         if h.y is None:
@@ -300,7 +315,7 @@ class Controller:
         self._batches.append(batch)
         self._pending = []
         self._pending_bytes = 0
-        if self.swap:
+        if self.swap and not self._in_backward:       # the batch compressed as the backward pass begins is its first
             self._resident.append(batch)
             self._resident_sum += batch.nbytes
             while self._resident and self._resident_sum > self.resident_bytes:
