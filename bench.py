@@ -697,6 +697,29 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
     res["compress_4bit_no_dedup"] = level(4)
     res["compress_4bit"] = level(4, dedup=True)
     res["compress_2bit"] = level(2, dedup=True)
+    # bits from the paper's adaptive algorithm: sensitivities by Alg. 1 (L + 1 seeded passes on this batch),
+    # widths by Eq. (ilp) at an average of 3 bits
+    ctl = Controller(params, group_size=256, bits=4, seed=0, min_numel=1 << 14, dedup=True)
+
+    def fwdbwd():
+        opt.zero_grad(set_to_none=True)
+        with ctl.hooks():
+            loss = (model(x) - target).float().pow(2).mean()
+        loss.backward()
+        return [p.grad for p in params]
+    t0 = time.perf_counter()
+    sens = ctl.compute_sensitivities(fwdbwd)
+    adapted = ctl.adapt(3.0)
+    torch.cuda.synchronize()
+    t_adapt = time.perf_counter() - t0
+    res["compress_adaptive_avg3"] = run(ctl, steps, warmup)
+    res["compress_adaptive_avg3"].update({
+        "context_tensors": int(len(adapted)), "adapt_seconds": round(t_adapt, 2),
+        "bits_histogram": {str(k): int((adapted == k).sum()) for k in (1, 2, 4, 8)},
+        "sensitivity_min_max": [float(sens.min()), float(sens.max())]})
+    del ctl
+    gc.collect()
+    torch.cuda.empty_cache()
     res["compress_4bit_swap"] = level(4, dedup=True, swap=True)
     res["compress_4bit_swap_limit_384MB"] = level(4, dedup=True, swap=True, swap_limit_bytes=384 << 20)
     res["compress_2bit_swap"] = level(2, dedup=True, swap=True)
