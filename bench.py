@@ -721,9 +721,9 @@ def bench_hooks_transformer(args, gact, torch, np, dev) -> int:
     gc.collect()
     torch.cuda.empty_cache()
     res["compress_4bit_swap"] = level(4, dedup=True, swap=True)
-    res["compress_4bit_swap_limit_384MB"] = level(4, dedup=True, swap=True, swap_limit_bytes=384 << 20)
+    res["compress_4bit_swap_inflight_4"] = level(4, dedup=True, swap=True, swap_inflight_batches=4)
+    res["compress_4bit_swap_inflight_12"] = level(4, dedup=True, swap=True, swap_inflight_batches=12)
     res["compress_2bit_swap"] = level(2, dedup=True, swap=True)
-    res["compress_2bit_swap_limit_192MB"] = level(2, dedup=True, swap=True, swap_limit_bytes=192 << 20)
     res["compress_4bit_swap_strict"] = level(4, dedup=True, swap=True, keep_until_copied=False)
     ref = res["no_hooks"]
     for k, r in res.items():

@@ -107,10 +107,18 @@ class Controller:
                                   needs last).  A volume that PCIe carries within the forward pass costs
                                   little; beyond it the backward pass is fed at the PCIe rate
     keep_until_copied             True: a swapped batch's device copy is let go only when its swap-out is seen
-                                  finished; the backward pass uses the most recent batches from the device
-                                  while their swap-outs are still under way (faster, and the peak follows
-                                  what PCIe manages).  False: let go at once; the backward pass waits for
-                                  every swap-out and fetches every batch back (lowest peak)
+                                  finished; the backward pass uses the most recent batches (those still
+                                  under way, at most `swap_inflight_batches`) from the device.  False: let
+                                  go at once; the backward pass waits for every swap-out and fetches every
+                                  batch back
+    swap_inflight_batches         swap-outs that may be unfinished at a time; the host waits for the oldest
+                                  before it compresses the next batch, which bounds the compressed data
+                                  on the device during the forward pass and paces it by PCIe when more is
+                                  swapped than PCIe carries
+    release_after_use             True: a batch that lives on the device is freed once the backward pass has
+                                  decompressed all its tensors (autograd frees a saved tensor the same way
+                                  unless the graph is retained).  False: kept until the next iteration, for
+                                  a second backward pass through a retained graph
     """
 
     def __init__(self, params: Sequence[torch.Tensor] = (), group_size: int = 256, bits: int = 4,
@@ -118,7 +126,8 @@ class Controller:
                  batch_tensors: int = 32, batch_bytes: int = 128 << 20, ahead_tensors: int = 32,
                  ahead_bytes: int = 128 << 20, resident_bytes: int = 0, swap_workgroups: int = 16,
                  prefetch_batches: int = 8, swap_limit_bytes: Optional[int] = None,
-                 keep_until_copied: bool = True):
+                 keep_until_copied: bool = True, release_after_use: bool = True,
+                 swap_inflight_batches: int = 8):
         self.group_size = group_size
         self.default_bits = bits
         self.base_seed = seed
@@ -139,6 +148,8 @@ class Controller:
         self.prefetch_batches = max(1, prefetch_batches)
         self.swap_limit_bytes = swap_limit_bytes
         self.keep_until_copied = keep_until_copied
+        self.release_after_use = release_after_use
+        self.swap_inflight_batches = max(1, swap_inflight_batches)
         self._in_backward = False
         self._swapped_bytes = 0
         self.param_ptrs = {p.data_ptr() for p in params}
@@ -180,8 +191,7 @@ class Controller:
         self.numel = []
 
     def release(self) -> None:
-        """Drop the compressed buffers of the last iteration (they are kept after the backward pass so
-        that a second backward pass through a retained graph still finds them)."""
+        """Drop what is left of the last iteration's compressed buffers."""
         self._arena_used = 0
         self._swapped_bytes = 0
         self._handles = []
@@ -250,9 +260,8 @@ class Controller:
             h, shape = h.base, h.shape
         if not isinstance(h, _Packed):
             return h
-        self._in_backward = True
-        if h.batch is None:
-            self._flush()                            # the backward pass has begun
+        if not self._in_backward:
+            self._begin_backward()
         if h.y is None:
             self._decompress_ahead(h)
         # one decompression serves every operator that saved the tensor; the last of them takes it away
@@ -261,6 +270,12 @@ class Controller:
         if h.left <= 0:
             h.y = None
         return y.view(h.shape if shape is None else shape)
+
+    def _begin_backward(self) -> None:
+        """First request for a saved tensor: compress what is pending; that batch stays on the device,
+        it is the first one needed."""
+        self._in_backward = True
+        self._flush()
 
     def hooks(self):
         """Context manager: ``with controller.hooks(): loss = model(x)``."""
@@ -289,6 +304,14 @@ class Controller:
             total += pb + 2 * mb
         dev = pend[0].x.device
         if self.swap:
+            # At most `swap_inflight_batches` swap-outs unfinished: the host waits here for the oldest.  The
+            # host runs ahead of the GPU, and memory is handed out in host order: without the wait nothing
+            # that is being swapped out has been given back by the time the forward pass has been enqueued,
+            # and the peak is that of a run without swapping.  With it the compressed data on the device
+            # are bounded by this many batches (plus those that are not swapped at all).
+            while len(self._out_inflight) >= self.swap_inflight_batches:
+                self._out_inflight[0].out_event.synchronize()
+                self._reap_out()
             self._reap_out()
         blob = torch.empty(total, dtype=torch.uint8, device=dev)
         base = blob.data_ptr()
@@ -334,7 +357,7 @@ class Controller:
         while k >= 0 and len(todo) < self.ahead_tensors:
             g = self._handles[k]
             k -= 1
-            if g is None or g.done or g.y is not None or g.batch is None:
+            if g is None or g.done or g.y is not None or g.batch is None or (g.batch.blob is None and g.batch.host is None):
                 continue
             size = g.n * (2 if g.dtype == torch.bfloat16 else 4)
             if nbytes + size > self.ahead_bytes:
@@ -344,8 +367,11 @@ class Controller:
                 break
             todo.append(g)
             nbytes += size
+        if h.batch.blob is None and h.batch.host is None:
+            raise RuntimeError("the compressed data of this tensor were released after their first use in the "
+                               "backward pass; for a second pass through a retained graph construct the "
+                               "Controller with release_after_use=False")
         if self.swap:
-            self._reap_out(keep_from=h.batch.index - self.prefetch_batches)
             self._ensure_on_device(h.batch)
         main = torch.cuda.current_stream()
         descs = self._descs
@@ -371,18 +397,30 @@ class Controller:
                                        ws.numel(), main.cuda_stream)
         if rc != GACT_OK:
             raise GactError(rc, "gact_decompress_multi")
+        # A batch goes once all its tensors have been decompressed (the launch above is ordered before
+        # the release).  A swapped batch leaves the device and a second unpack fetches it again; one that
+        # lives on the device only is gone for good unless `release_after_use` is off.
+        for g in todo:
+            b = g.batch
+            if b.remaining <= 0 and b.blob is not None:
+                if b.host is not None:
+                    b.blob, b.in_event, b.remaining = None, None, b.count
+                elif self.release_after_use:
+                    b.blob = None
         if self.swap:
             # prefetch the batches packed before this one while it is being used: several, so that the
             # copies run back to back whether the backward pass dwells on a batch or rushes through it
+            # (batches still on the device need no fetch and do not count, so the first fetches start
+            # with the backward pass even when the most recent batches never left)
             i = h.batch.index
-            for j in range(i - 1, max(i - 1 - self.prefetch_batches, -1), -1):
-                self._start_swap_in(self._batches[j])
-            # a swapped batch leaves the device again once all its tensors have been handed back
-            # (the launch above is ordered before the release; a second unpack fetches it again)
-            for g in todo:
-                b = g.batch
-                if b.remaining <= 0 and b.host is not None and b.blob is not None:
-                    b.blob, b.in_event, b.remaining = None, None, b.count
+            ahead = sum(1 for b in self._batches[:i] if b.in_event is not None)
+            j = i - 1
+            while ahead < self.prefetch_batches and j >= 0:
+                b = self._batches[j]
+                if b.blob is None and b.host is not None:
+                    self._start_swap_in(b)
+                    ahead += 1
+                j -= 1
 
     # ------------------------------------------------------------------- swap
     def _pinned(self, nbytes: int) -> torch.Tensor:
@@ -410,23 +448,20 @@ class Controller:
             batch.out_event.record()
         self._swapped_bytes += batch.nbytes
         batch.host = buf
-        if self.keep_until_copied:
-            self._out_inflight.append(batch)            # the device copy stays until the copy is seen finished
-        else:
+        self._out_inflight.append(batch)
+        if not self.keep_until_copied:
             batch.blob = None                           # the allocator reuses the memory once the copy is through
 
-    def _reap_out(self, keep_from: Optional[int] = None) -> None:
-        """Let go of the device copies of batches whose swap-out has finished.  Until then the memory
-        cannot be reused anyway, so the copy on the device costs nothing, and a batch the backward
-        pass reaches while its swap-out is still under way (the most recent ones: the first it needs
-        are the last that were sent) is used from the device without waiting for PCIe at all.  In the
-        backward pass batches from index `keep_from` on stay for the same reason: they are inside the
-        prefetch window and would be fetched back at once."""
+    def _reap_out(self) -> None:
+        """Forward pass: let go of the device copies of batches whose swap-out has finished.  Until then
+        the memory cannot be reused anyway, so the copy on the device costs nothing, and a batch the
+        backward pass reaches while its swap-out is still under way (the most recent ones: the first it
+        needs are the last that were sent) is used from the device without waiting for PCIe at all.
+        Nothing is let go during the backward pass: memory only falls there, and a batch let go would
+        be fetched back soon after."""
         q = self._out_inflight
         while q and q[0].out_event.query():
-            b = q.pop(0)
-            if keep_from is None or b.index < keep_from:
-                b.blob = None
+            q.pop(0).blob = None
 
     def _start_swap_in(self, batch: _Batch) -> None:
         if batch.blob is not None or batch.host is None:

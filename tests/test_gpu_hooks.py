@@ -256,16 +256,21 @@ def test_swap_with_resident_tail_and_small_batches_gives_identical_gradients(gac
         torch.cuda.synchronize()
         for ga, gb in zip(a, b):
             assert torch.equal(ga, gb)
-    # a cap on the bytes swapped per iteration, three batches fetched ahead
+    # a cap on the bytes swapped per iteration, three batches fetched ahead.  With device copies kept until
+    # their swap-out is seen finished, how many batches end up on the host depends on timing (those still
+    # under way when the backward pass begins stay on the device and their copies are dropped); with the
+    # copies let go at once it is exact.
     for backlog in (0, 40 << 10, 1 << 30):
-        ctrl = Controller(model.parameters(), bits=4, seed=9, swap=True, batch_tensors=1, ahead_tensors=1,
-                          swap_limit_bytes=backlog, prefetch_batches=3)
-        b = grads(model, x, y, ctrl)
-        torch.cuda.synchronize()
-        for ga, gb in zip(a, b):
-            assert torch.equal(ga, gb)
-        swapped = sum(bt.host is not None for bt in ctrl._batches)
-        assert swapped == {0: 0, 40 << 10: 1}.get(backlog, len(ctrl._batches))
+        for keep in (True, False):
+            ctrl = Controller(model.parameters(), bits=4, seed=9, swap=True, batch_tensors=1, ahead_tensors=1,
+                              swap_limit_bytes=backlog, prefetch_batches=3, keep_until_copied=keep)
+            b = grads(model, x, y, ctrl)
+            torch.cuda.synchronize()
+            for ga, gb in zip(a, b):
+                assert torch.equal(ga, gb)
+            swapped = sum(bt.host is not None for bt in ctrl._batches)
+            exact = {0: 0, 40 << 10: 1}.get(backlog, len(ctrl._batches))
+            assert swapped == exact if not keep else swapped <= exact
 
 
 def test_compressed_buffers_of_an_iteration_are_released_at_the_next(gact):
@@ -287,3 +292,29 @@ def test_compressed_buffers_of_an_iteration_are_released_at_the_next(gact):
         assert at_start[1] == at_start[2] == at_start[3]
     finally:
         gc.enable()
+
+
+def test_a_retained_graph_can_be_walked_twice_only_when_the_buffers_are_kept(gact):
+    """Compressed batches are freed as the backward pass uses them up; a second pass through a retained
+    graph needs them kept (and gets the same gradients), otherwise it is told why it cannot run."""
+    from paper_2206_11357_amd.hooks import Controller
+    model, (x, y) = make_model(), batch()
+
+    def twice(ctrl):
+        model.zero_grad(set_to_none=True)
+        ctrl.begin_iteration()
+        with ctrl.hooks():
+            loss = torch.nn.functional.cross_entropy(model(x), y)
+        loss.backward(retain_graph=True)
+        first = [p.grad.detach().clone() for p in model.parameters()]
+        model.zero_grad(set_to_none=True)
+        loss.backward()
+        return first, [p.grad.detach().clone() for p in model.parameters()]
+    for swap in (False, True):
+        first, second = twice(Controller(model.parameters(), bits=4, seed=5, release_after_use=False, swap=swap,
+                                         batch_tensors=2, ahead_tensors=1, keep_until_copied=False))
+        torch.cuda.synchronize()
+        for a, b in zip(first, second):
+            assert torch.equal(a, b)
+    with pytest.raises(RuntimeError, match="release_after_use"):
+        twice(Controller(model.parameters(), bits=4, seed=5, batch_tensors=2, ahead_tensors=1))
