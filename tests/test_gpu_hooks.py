@@ -250,9 +250,11 @@ def test_swap_with_resident_tail_and_small_batches_gives_identical_gradients(gac
     from paper_2206_11357_amd.hooks import Controller
     model, (x, y) = make_model(), batch()
     a = grads(model, x, y, Controller(model.parameters(), bits=4, seed=9))
-    for resident, keep in ((0, True), (0, False), (40 << 10, True), (40 << 10, False), (1 << 30, True)):
+    for resident, keep, inflight in ((0, True, 8), (0, False, 8), (40 << 10, True, 8), (40 << 10, False, 1),
+                                     (1 << 30, True, 8), (0, True, 1), (0, False, 1)):
         b = grads(model, x, y, Controller(model.parameters(), bits=4, seed=9, swap=True, batch_tensors=2,
-                                          ahead_tensors=1, resident_bytes=resident, keep_until_copied=keep))
+                                          ahead_tensors=1, resident_bytes=resident, keep_until_copied=keep,
+                                          swap_inflight_batches=inflight))
         torch.cuda.synchronize()
         for ga, gb in zip(a, b):
             assert torch.equal(ga, gb)
